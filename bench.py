@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the vocabulary-layer hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input:
+p x vp_output_fwd, vp_combine_stats, p x vp_output_bwd (all p shards of the configuration run
+in sequence on the one GPU).  The headline workload is the Llama-like configuration
+(N=4096, h=4096, V=32000, p=8, bf16); the other configurations are timed briefly as well and
+reported under "per_config".  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  value = 6*N*h*V / step time (the paper's FLOP model for the output
+layer), in TFLOP/s.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+METRIC = "vocab-layer fwd+bwd TFLOP/s and tokens/s per GPU; % of bf16 MFMA peak"
+
+
+def dev(x):
+    import torch
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(x).cuda()
+
+
+def time_steps(step, steps, warmup):
+    """Returns (wall ms per step, event ms per step) for `steps` calls after `warmup` calls."""
+    import torch
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def profiled_steps(vp, step, steps):
+    """Per-kernel average launch duration (ms) over `steps` more steps, from HIP events the
+    library records around each of its kernel launches on the launch stream."""
+    import torch
+    torch.cuda.synchronize()
+    vp.vp_profile_enable(True)
+    try:
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        rec = vp.vp_profile_read()
+    finally:
+        vp.vp_profile_enable(False)
+    return {k: {"ms_per_launch": ms / n, "launches_per_step": n / steps, "ms_per_step": ms / steps}
+            for k, (ms, n) in rec.items()}
+
+
+def make_output_plan(vp, cfg, seeded_numpy):
+    """Inputs of an output-layer configuration in HBM.  seeded_numpy=True uses the host
+    generator shared with the oracle tests; otherwise tensors of the same distribution are
+    drawn on the GPU (only timed, never compared)."""
+    import torch
+    import synth_inputs as si
+    labels = si.make_labels(cfg)
+    if seeded_numpy:
+        H = dev(si.make_H(cfg))
+        Ws = [dev(si.make_W_shard(cfg, r)) for r in range(cfg.p)]
+    else:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(si.BASE_SEED)
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+        H = (torch.randn((cfg.N, cfg.h), generator=g, device="cuda") * cfg.h_std).to(tdt)
+        Ws = [(torch.randn((cfg.Vs, cfg.h), generator=g, device="cuda") * cfg.w_std).to(tdt) for _ in range(cfg.p)]
+    return vp.OutputLayerPlan(H, Ws, dev(labels), cfg.save_logits)
+
+
+def output_numbers(cfg, ms):
+    tflops = cfg.model_flops / (ms * 1e-3) / 1e12
+    hw_flops = cfg.model_flops * (1.0 if cfg.save_logits else 8.0 / 6.0)
+    return {
+        "ms_per_step": ms,
+        "model_tflops": tflops,
+        "hardware_tflops": hw_flops / (ms * 1e-3) / 1e12,
+        "pct_bf16_mfma_peak": 100.0 * tflops / BF16_MFMA_PEAK_TFLOPS if cfg.dtype == "bf16" else None,
+        "tokens_per_s": cfg.N / (ms * 1e-3),
+        "tokens_per_s_per_shard_device": cfg.N * cfg.p / (ms * 1e-3),
+    }
+
+
+def gemm_roofline(cfg, kernels):
+    """Roofline entry for the slowest of the bf16 MFMA GEMM kernels."""
+    names = [k for k in kernels if k.startswith("gemm_bf16")]
+    if not names:
+        return None
+    dom = max(names, key=lambda k: kernels[k]["ms_per_step"])
+    flops_per_launch = 2.0 * cfg.N * cfg.h * cfg.Vs
+    ach = flops_per_launch / (kernels[dom]["ms_per_launch"] * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": ach / BF16_MFMA_PEAK_TFLOPS, "flops_per_launch": flops_per_launch,
+            "avg_launch_ms": kernels[dom]["ms_per_launch"], "traffic": None}
+
+
+def cpu_baseline(cfg, sample_rows):
+    """The oracle (Algorithm 1 on the CPU, fp64) on the first `sample_rows` token rows of the
+    same inputs, all p shards, forward and backward."""
+    import synth_inputs as si
+    from oracle import vp_oracle as oc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    H = si.as_f64(si.make_H(cfg)[:sample_rows])
+    labels = si.make_labels(cfg)[:sample_rows]
+    Ws = [si.as_f64(si.make_W_shard(cfg, r)) for r in range(cfg.p)]
+    t0 = time.perf_counter()
+    out = oc.output_layer_alg1(H, Ws, labels)
+    dt = time.perf_counter() - t0
+    flops = 6.0 * sample_rows * cfg.h * cfg.V
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "seconds": dt, "loss_on_sample": float(out["loss"]),
+            "sample": "oracle.output_layer_alg1 (fp64) on the first %d of %d token rows of %s, all %d shards, "
+                      "forward + backward" % (sample_rows, cfg.N, cfg.name, cfg.p)}
+
+
+def bench_embedding(vp, cfg, steps, warmup):
+    import torch
+    import synth_inputs as si
+    ids = si.make_labels(cfg)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(si.BASE_SEED + 5)
+    tables = [(torch.randn((cfg.Vs, cfg.h), generator=g, device="cuda") * cfg.table_std).to(torch.bfloat16)
+              for _ in range(cfg.p)]
+    gout = (torch.randn((cfg.N, cfg.h), generator=g, device="cuda") * cfg.grad_std).to(torch.bfloat16)
+    plan = vp.EmbeddingPlan(tables, dev(ids), gout)
+    _, fwd_ms = time_steps(plan.forward, steps, warmup)
+    _, bwd_ms = time_steps(plan.backward, steps, warmup)
+    kern = profiled_steps(vp, lambda: (plan.forward(), plan.backward()), steps)
+    uniq = len(np.unique(ids))
+    fwd_bytes = cfg.p * cfg.N * cfg.h * 2 + cfg.N * cfg.h * 2 + cfg.p * cfg.N * 8
+    bwd_bytes = cfg.N * cfg.h * 2 + 2 * uniq * cfg.h * 4 + cfg.p * cfg.N * 8
+    return {
+        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "fwd_algorithmic_bytes": fwd_bytes, "bwd_algorithmic_bytes": bwd_bytes,
+        "fwd_GBs": fwd_bytes / (fwd_ms * 1e-3) / 1e9, "bwd_GBs": bwd_bytes / (bwd_ms * 1e-3) / 1e9,
+        "fwd_frac_hbm_peak": fwd_bytes / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "bwd_frac_hbm_peak": bwd_bytes / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "tokens_per_s_fwd_bwd": cfg.N / ((fwd_ms + bwd_ms) * 1e-3),
+        "unique_ids": uniq, "kernels": kern,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg2_llama", help="headline output-layer configuration")
+    ap.add_argument("--only-headline", action="store_true", help="skip the per_config section")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the p shards of a configuration run in sequence "
+              "on it); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2411_05288_amd as vp
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = si.CONFIGS[args.config]
+
+    plan = make_output_plan(vp, cfg, seeded_numpy=True)
+    wall_ms, ev_ms = time_steps(plan.step, args.steps, args.warmup)
+    kernels = profiled_steps(vp, plan.step, args.steps)
+    nums = output_numbers(cfg, wall_ms)
+    loss = float(plan.loss.cpu()[0])
+    del plan
+    torch.cuda.empty_cache()
+
+    per_config = {}
+    if not args.only_headline:
+        for name, c in si.CONFIGS.items():
+            if name == args.config:
+                per_config[name] = dict(nums, kernels=kernels, roofline=gemm_roofline(cfg, kernels))
+                continue
+            k_steps = max(3, min(args.steps, 10))
+            if isinstance(c, si.EmbedConfig):
+                per_config[name] = bench_embedding(vp, c, k_steps, 3)
+                continue
+            pl = make_output_plan(vp, c, seeded_numpy=False)
+            w_ms, _ = time_steps(pl.step, k_steps, 2)
+            kern = profiled_steps(vp, pl.step, k_steps)
+            per_config[name] = dict(output_numbers(c, w_ms), kernels=kern, roofline=gemm_roofline(c, kern))
+            del pl
+            torch.cuda.empty_cache()
+
+    out = {
+        "metric": METRIC,
+        "value": nums["model_tflops"],
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "event_ms_per_step": ev_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "tokens_per_s": nums["tokens_per_s"],
+        "tokens_per_s_per_shard_device": nums["tokens_per_s_per_shard_device"],
+        "pct_bf16_mfma_peak": nums["pct_bf16_mfma_peak"],
+        "loss": loss,
+        "config": {"workload": "%s: N=%d h=%d V=%d p=%d Vs=%d %s, logits %s; fwd + combine + bwd of all p shards "
+                               "in sequence on one GPU" % (cfg.name, cfg.N, cfg.h, cfg.V, cfg.p, cfg.Vs, cfg.dtype,
+                                                           "stored" if cfg.save_logits else "recomputed"),
+                   "N": cfg.N, "h": cfg.h, "V": cfg.V, "p": cfg.p, "Vs": cfg.Vs,
+                   "model_flops_per_step": cfg.model_flops},
+        "roofline": gemm_roofline(cfg, kernels),
+        "kernels": kernels,
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(cfg, args.cpu_sample_rows),
+        "per_config": per_config,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,168 @@
+/*
+ * vp.h - C ABI of libvp: one device's shard of the vocabulary layers of Vocabulary
+ * Parallelism (arXiv 2411.05288) on AMD MI355X (gfx950).
+ *
+ * Notation (paper, section 4): N = b*s token rows, h hidden size, V vocabulary size,
+ * p shards, Vs rows of the vocabulary owned by this shard, shard_offset the global id of
+ * the shard's first row.  X (here H) is [N, h]; the shard of the embedding weights W is
+ * [Vs, h]; Y = X W^T are the logits; m_i and sum_i the row maximum and the row sum of
+ * exponentials; g_i the label of token i.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, dense row-major,
+ *     16-byte aligned.  The library allocates nothing, frees nothing and keeps no state
+ *     between calls; scratch memory is the caller's `workspace`, at least
+ *     vp_workspace_bytes(...) bytes, 256-byte aligned, contents undefined on entry/exit.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and return; there is no host synchronisation inside.
+ *   - Arguments are validated on the host before anything is launched.  An invalid
+ *     argument returns an error code and launches nothing.  Nothing is thrown or aborted
+ *     across this boundary.
+ *   - `dt` is the storage type of H, W, the embedding table, the stored logits and the
+ *     incoming embedding gradient.  Statistics, the loss and all gradients leaving the
+ *     library are fp32.  With VP_BF16 the products are bf16 x bf16 MFMA with fp32
+ *     accumulation; with VP_F32 everything is computed in fp32.
+ *   - Labels / token ids are global vocabulary ids (int64).  An id outside the shard's
+ *     range [shard_offset, shard_offset + Vs) - including ids outside [0, V) - is treated
+ *     as "not owned": target logit 0, all-zero one-hot row, zero output row, no scatter.
+ *   - Sizes: 1 <= N, h, Vs and N*Vs, N*h, Vs*h < 2^31 elements each.
+ */
+#ifndef VP_H_
+#define VP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VP_OK = 0,
+    VP_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, bad enum, misaligned pointer */
+    VP_ERR_UNSUPPORTED = 2, /* valid request outside the implemented size limits */
+    VP_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than vp_workspace_bytes() */
+    VP_ERR_DEVICE = 4       /* the HIP runtime reported an error at launch */
+} vp_status;
+
+typedef enum { VP_F32 = 0, VP_BF16 = 1 } vp_dtype;
+
+typedef enum {
+    VP_CALL_OUTPUT_FWD = 0,
+    VP_CALL_COMBINE_STATS = 1,
+    VP_CALL_OUTPUT_BWD = 2,
+    VP_CALL_EMBED_FWD = 3,
+    VP_CALL_EMBED_BWD = 4
+} vp_call;
+
+/* flags */
+enum {
+    VP_SAVE_LOGITS = 1u /* fwd: store the logits; bwd: the stored logits are supplied */
+};
+
+/* Library version (major*10000 + minor*100 + patch). Host-only, no device work. */
+int vp_version(void);
+
+/* Static, human-readable name of a status code. */
+const char* vp_status_string(vp_status s);
+
+/*
+ * Bytes of scratch the given call needs for these sizes (0 if none).  Host-only.
+ * Returns (size_t)-1 for invalid arguments.
+ */
+size_t vp_workspace_bytes(vp_call which, int64_t N, int64_t h, int64_t Vs, vp_dtype dt, uint32_t flags);
+
+/*
+ * Pass S of Algorithm 1 (section 4.3) for one shard: Y = H W_shard^T over the shard's Vs
+ * vocabulary rows, fused with the shard-local softmax statistics, so the logits are never
+ * re-read:
+ *     local_max[i]    = m'_i   = max_k Y_ik
+ *     local_sumexp[i] = sum'_i = sum_k exp(Y_ik - m'_i)
+ *     local_target[i] = Y[i, labels[i] - shard_offset] if the shard owns labels[i], else 0
+ * The paper's softmax' matrix is not materialised.  If logits_out != NULL (flag
+ * VP_SAVE_LOGITS must then be set) Y is also stored there as [N, Vs] in type `dt`.
+ *   H [N,h], W_shard [Vs,h] : in, type dt.     labels [N] : in, int64.
+ *   local_* [N] : out, fp32.                   logits_out : out or NULL.
+ */
+vp_status vp_output_fwd(const void* H, const void* W_shard, const int64_t* labels,
+                        int64_t N, int64_t h, int64_t Vs, int64_t shard_offset,
+                        vp_dtype dt, uint32_t flags,
+                        float* local_max, float* local_sumexp, float* local_target,
+                        void* logits_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Barrier C1 of Algorithm 1 (section 4.3) as an on-device fold over the p shards' rows
+ * (it stands in for the two all-reduces):
+ *     m_i   = max_r m'_{r,i}
+ *     sum_i = sum_r sum'_{r,i} * exp(m'_{r,i} - m_i)      (ascending r)
+ *     loss_i = m_i + ln(sum_i) - sum_r t'_{r,i};   loss_mean = (1/N) sum_i loss_i
+ * The mean is taken with one fixed reduction tree, so results repeat bit for bit.
+ *   local_* [p,N] : in, fp32 (row r = shard r's vp_output_fwd outputs).
+ *   global_max, global_sumexp [N] : out.  loss_per_row [N] : out or NULL.  loss_mean [1] : out.
+ */
+vp_status vp_combine_stats(const float* local_max, const float* local_sumexp, const float* local_target,
+                           int32_t p, int64_t N,
+                           float* global_max, float* global_sumexp,
+                           float* loss_per_row, float* loss_mean, void* stream);
+
+/*
+ * Pass T of Algorithm 1 plus this shard's term of the reduce C2 (section 4.3; gradients
+ * of section 4.2):
+ *     D_ij      = ( exp(Y_ij - m_i) / sum_i  -  [labels[i] == shard_offset + j] ) * grad_scale
+ *                 (equal to softmax' * sum' e^{m'-m} / sum - G, the rescale identity)
+ *     dH_accum += D W_shard          (fp32, accumulate: the caller zeroes it once per
+ *                                     microbatch; calling the p shards in ascending order
+ *                                     is the deterministic reduce)
+ *     dW_shard  = D^T H              (fp32, overwritten)
+ * grad_scale = 1/N gives the gradients of the mean loss, 1 the paper's unscaled form.
+ * logits_saved != NULL (with VP_SAVE_LOGITS): Y is read from there ([N,Vs], type dt);
+ * NULL: Y is recomputed from H and W_shard.
+ */
+vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* labels,
+                        int64_t N, int64_t h, int64_t Vs, int64_t shard_offset,
+                        vp_dtype dt, uint32_t flags,
+                        const float* global_max, const float* global_sumexp,
+                        const void* logits_saved, float grad_scale,
+                        float* dH_accum, float* dW_shard,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Input layer forward on one shard (appendix C): the full-size [N,h] output, row i being
+ * table_shard[ids[i] - shard_offset] when the shard owns ids[i] and all +0 otherwise, so
+ * that the sum over shards is the embedding lookup.  Pure data movement, bit exact.
+ *   table_shard [Vs,h] : in, type dt.  ids [N] : in.  out [N,h] : out, type dt.
+ */
+vp_status vp_embed_fwd(const void* table_shard, const int64_t* ids,
+                       int64_t N, int64_t h, int64_t Vs, int64_t shard_offset, vp_dtype dt,
+                       void* out, void* stream);
+
+/*
+ * Input layer backward on one shard (appendix C): scatter-add of the output gradient,
+ *     dtable_shard[ids[i] - shard_offset, :] += (float) grad_out[i, :]   for owned ids,
+ * with repeated ids accumulated in increasing token position i.  No atomics: tokens are
+ * grouped by row with a sort and every row is summed by one workgroup, so the result is
+ * bit-identical from run to run.
+ *   grad_out [N,h] : in, type dt.  dtable_shard [Vs,h] : in/out, fp32, accumulate.
+ * Limit: N <= 2^24.
+ */
+vp_status vp_embed_bwd(const void* grad_out, const int64_t* ids,
+                       int64_t N, int64_t h, int64_t Vs, int64_t shard_offset, vp_dtype dt,
+                       float* dtable_shard, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Measurement aid, not part of the method.  While enabled, every kernel launch made by the
+ * entry points above is bracketed by two HIP events on the launch stream (events are created
+ * on demand and pooled; this is the only state the library ever holds, and none exists while
+ * timing is off, the default).  vp_profile_read waits for the recorded events, writes the
+ * summed elapsed milliseconds and the launch count per kernel id into the two host arrays
+ * (length n >= vp_profile_kernel_count()), and clears the records.
+ */
+int vp_profile_kernel_count(void);
+const char* vp_profile_kernel_name(int id);
+vp_status vp_profile_enable(int on);
+vp_status vp_profile_read(double* ms_total, int64_t* launches, int n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VP_H_ */

@@ -1,0 +1,221 @@
+// extern "C" entry points of libvp: argument validation, workspace carving and the order of
+// kernel launches for each pass.  No allocation, no synchronisation, no state.
+#include "vp_internal.h"
+
+using namespace vp;
+
+namespace {
+
+constexpr int64_t MAX_ELEMS = (int64_t)1 << 31;
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+bool sizes_ok(int64_t N, int64_t h, int64_t Vs) { return N >= 1 && h >= 1 && Vs >= 1; }
+
+bool sizes_supported(int64_t N, int64_t h, int64_t Vs) {
+    return N < MAX_ELEMS && h < MAX_ELEMS && Vs < MAX_ELEMS && N * Vs < MAX_ELEMS && N * h < MAX_ELEMS &&
+           Vs * h < MAX_ELEMS;
+}
+
+bool dtype_ok(vp_dtype dt) { return dt == VP_F32 || dt == VP_BF16; }
+
+int64_t fwd_tiles(int64_t Vs) { return ceil_div(Vs, GEMM_BN); }
+
+vp_status dev(hipError_t e) { return e == hipSuccess ? VP_OK : VP_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+int vp_version(void) { return 100; }
+
+const char* vp_status_string(vp_status s) {
+    switch (s) {
+        case VP_OK: return "VP_OK";
+        case VP_ERR_INVALID_ARG: return "VP_ERR_INVALID_ARG";
+        case VP_ERR_UNSUPPORTED: return "VP_ERR_UNSUPPORTED";
+        case VP_ERR_WORKSPACE: return "VP_ERR_WORKSPACE";
+        case VP_ERR_DEVICE: return "VP_ERR_DEVICE";
+    }
+    return "VP_ERR_UNKNOWN";
+}
+
+size_t vp_workspace_bytes(vp_call which, int64_t N, int64_t h, int64_t Vs, vp_dtype dt, uint32_t flags) {
+    if (!dtype_ok(dt) || (flags & ~(uint32_t)VP_SAVE_LOGITS)) return (size_t)-1;
+    switch (which) {
+        case VP_CALL_OUTPUT_FWD:
+            if (!sizes_ok(N, h, Vs) || !sizes_supported(N, h, Vs)) return (size_t)-1;
+            if (dt == VP_BF16) return align_up((size_t)(2 * fwd_tiles(Vs) + 1) * N * sizeof(float), 256);
+            // fp32: the logits live in the workspace unless the caller keeps them
+            return (flags & VP_SAVE_LOGITS) ? 0 : align_up((size_t)N * Vs * sizeof(float), 256);
+        case VP_CALL_OUTPUT_BWD:
+            if (!sizes_ok(N, h, Vs) || !sizes_supported(N, h, Vs)) return (size_t)-1;
+            return align_up((size_t)N * Vs * (dt == VP_BF16 ? 2 : 4), 256);
+        case VP_CALL_EMBED_BWD:
+            if (N < 1 || N > ((int64_t)1 << 24)) return (size_t)-1;
+            return align_up(embed_bwd_workspace(N), 256);
+        case VP_CALL_COMBINE_STATS:
+        case VP_CALL_EMBED_FWD:
+            return 0;
+    }
+    return (size_t)-1;
+}
+
+vp_status vp_output_fwd(const void* H, const void* W_shard, const int64_t* labels, int64_t N, int64_t h, int64_t Vs,
+                        int64_t shard_offset, vp_dtype dt, uint32_t flags, float* local_max, float* local_sumexp,
+                        float* local_target, void* logits_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!H || !W_shard || !labels || !local_max || !local_sumexp || !local_target) return VP_ERR_INVALID_ARG;
+    if (!sizes_ok(N, h, Vs) || !dtype_ok(dt) || shard_offset < 0) return VP_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)VP_SAVE_LOGITS) return VP_ERR_INVALID_ARG;
+    if (((flags & VP_SAVE_LOGITS) != 0) != (logits_out != nullptr)) return VP_ERR_INVALID_ARG;
+    if (!aligned16(H) || !aligned16(W_shard) || !aligned16(logits_out) || !aligned16(workspace))
+        return VP_ERR_INVALID_ARG;
+    if (!sizes_supported(N, h, Vs)) return VP_ERR_UNSUPPORTED;
+    const size_t need = vp_workspace_bytes(VP_CALL_OUTPUT_FWD, N, h, Vs, dt, flags);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return VP_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+
+    if (dt == VP_BF16) {
+        const int64_t tiles = fwd_tiles(Vs);
+        float* pm = (float*)workspace;
+        float* ps = pm + tiles * N;
+        float* pt = ps + tiles * N;
+        GemmBf16Params g{};
+        g.A = (const u16*)H; g.B = (const u16*)W_shard;
+        g.M = (int)N; g.N = (int)Vs; g.K = (int)h;
+        g.lda = (int)h; g.ldb = (int)h;
+        g.a_kcontig = 1; g.b_kcontig = 1;
+        g.vec_ok = (h % 8 == 0) ? 1 : 0;
+        g.epi = Epi::FwdStats;
+        g.Y = (u16*)logits_out; g.ldy = (int)Vs;
+        g.labels = labels; g.shard_offset = shard_offset;
+        g.part_max = pm; g.part_sum = ps; g.part_tgt = pt;
+        hipError_t e = launch_gemm_bf16(g, st);
+        if (e != hipSuccess) return VP_ERR_DEVICE;
+        return dev(launch_fold_partials(pm, ps, pt, (int)tiles, (int)N, labels, shard_offset, (int)Vs, local_max,
+                                        local_sumexp, local_target, st));
+    }
+    float* Y = logits_out ? (float*)logits_out : (float*)workspace;
+    hipError_t e = launch_gemm_f32((const float*)H, h, 1, (const float*)W_shard, h, 1, Y, Vs, (int)N, (int)Vs, (int)h,
+                                   false, st);
+    if (e != hipSuccess) return VP_ERR_DEVICE;
+    return dev(launch_row_stats_f32(Y, Vs, labels, shard_offset, (int)N, (int)Vs, local_max, local_sumexp,
+                                    local_target, st));
+}
+
+vp_status vp_combine_stats(const float* local_max, const float* local_sumexp, const float* local_target, int32_t p,
+                           int64_t N, float* global_max, float* global_sumexp, float* loss_per_row, float* loss_mean,
+                           void* stream) {
+    if (!local_max || !local_sumexp || !local_target || !global_max || !global_sumexp || !loss_mean)
+        return VP_ERR_INVALID_ARG;
+    if (p < 1 || N < 1) return VP_ERR_INVALID_ARG;
+    if (N >= MAX_ELEMS || (int64_t)p * N >= MAX_ELEMS) return VP_ERR_UNSUPPORTED;
+    return dev(launch_combine(local_max, local_sumexp, local_target, p, (int)N, global_max, global_sumexp,
+                              loss_per_row, loss_mean, (hipStream_t)stream));
+}
+
+vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* labels, int64_t N, int64_t h, int64_t Vs,
+                        int64_t shard_offset, vp_dtype dt, uint32_t flags, const float* global_max,
+                        const float* global_sumexp, const void* logits_saved, float grad_scale, float* dH_accum,
+                        float* dW_shard, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!H || !W_shard || !labels || !global_max || !global_sumexp || !dH_accum || !dW_shard)
+        return VP_ERR_INVALID_ARG;
+    if (!sizes_ok(N, h, Vs) || !dtype_ok(dt) || shard_offset < 0) return VP_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)VP_SAVE_LOGITS) return VP_ERR_INVALID_ARG;
+    if (((flags & VP_SAVE_LOGITS) != 0) != (logits_saved != nullptr)) return VP_ERR_INVALID_ARG;
+    if (!aligned16(H) || !aligned16(W_shard) || !aligned16(logits_saved) || !aligned16(workspace) ||
+        !aligned16(dH_accum) || !aligned16(dW_shard))
+        return VP_ERR_INVALID_ARG;
+    if (!sizes_supported(N, h, Vs)) return VP_ERR_UNSUPPORTED;
+    const size_t need = vp_workspace_bytes(VP_CALL_OUTPUT_BWD, N, h, Vs, dt, flags);
+    if (!workspace || workspace_bytes < need) return VP_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+
+    if (dt == VP_BF16) {
+        u16* D = (u16*)workspace;
+        const int vec_ok = (h % 8 == 0 && Vs % 8 == 0) ? 1 : 0;
+        if (logits_saved) {
+            e = launch_dlogits(logits_saved, D, 1, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N,
+                               (int)Vs, st);
+        } else {
+            GemmBf16Params g{};
+            g.A = (const u16*)H; g.B = (const u16*)W_shard;
+            g.M = (int)N; g.N = (int)Vs; g.K = (int)h;
+            g.lda = (int)h; g.ldb = (int)h;
+            g.a_kcontig = 1; g.b_kcontig = 1;
+            g.vec_ok = (h % 8 == 0) ? 1 : 0;
+            g.epi = Epi::DLogits;
+            g.Y = D; g.ldy = (int)Vs;
+            g.labels = labels; g.shard_offset = shard_offset;
+            g.gmax = global_max; g.gsum = global_sumexp; g.scale = grad_scale;
+            e = launch_gemm_bf16(g, st);
+        }
+        if (e != hipSuccess) return VP_ERR_DEVICE;
+        {   // dH += D W_shard : M = N tokens, N = h, K = Vs; W_shard is stored [K][N]
+            GemmBf16Params g{};
+            g.A = D; g.B = (const u16*)W_shard;
+            g.M = (int)N; g.N = (int)h; g.K = (int)Vs;
+            g.lda = (int)Vs; g.ldb = (int)h;
+            g.a_kcontig = 1; g.b_kcontig = 0;
+            g.vec_ok = vec_ok;
+            g.epi = Epi::AccumF32;
+            g.C = dH_accum; g.ldc = (int)h;
+            e = launch_gemm_bf16(g, st);
+            if (e != hipSuccess) return VP_ERR_DEVICE;
+        }
+        {   // dW = D^T H : M = Vs, N = h, K = N tokens; D is stored [K][M], H is stored [K][N]
+            GemmBf16Params g{};
+            g.A = D; g.B = (const u16*)H;
+            g.M = (int)Vs; g.N = (int)h; g.K = (int)N;
+            g.lda = (int)Vs; g.ldb = (int)h;
+            g.a_kcontig = 0; g.b_kcontig = 0;
+            g.vec_ok = vec_ok;
+            g.epi = Epi::StoreF32;
+            g.C = dW_shard; g.ldc = (int)h;
+            e = launch_gemm_bf16(g, st);
+        }
+        return dev(e);
+    }
+
+    // fp32: every step in fp32
+    float* D = (float*)workspace;
+    const float* Y = (const float*)logits_saved;
+    if (!Y) {
+        e = launch_gemm_f32((const float*)H, h, 1, (const float*)W_shard, h, 1, D, Vs, (int)N, (int)Vs, (int)h, false,
+                            st);
+        if (e != hipSuccess) return VP_ERR_DEVICE;
+        Y = D;   // D is formed in place
+    }
+    e = launch_dlogits(Y, D, 0, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N, (int)Vs, st);
+    if (e != hipSuccess) return VP_ERR_DEVICE;
+    e = launch_gemm_f32(D, Vs, 1, (const float*)W_shard, 1, h, dH_accum, h, (int)N, (int)h, (int)Vs, true, st);
+    if (e != hipSuccess) return VP_ERR_DEVICE;
+    e = launch_gemm_f32(D, 1, Vs, (const float*)H, 1, h, dW_shard, h, (int)Vs, (int)h, (int)N, false, st);
+    return dev(e);
+}
+
+vp_status vp_embed_fwd(const void* table_shard, const int64_t* ids, int64_t N, int64_t h, int64_t Vs,
+                       int64_t shard_offset, vp_dtype dt, void* out, void* stream) {
+    if (!table_shard || !ids || !out) return VP_ERR_INVALID_ARG;
+    if (!sizes_ok(N, h, Vs) || !dtype_ok(dt) || shard_offset < 0) return VP_ERR_INVALID_ARG;
+    if (!aligned16(table_shard) || !aligned16(out)) return VP_ERR_INVALID_ARG;
+    if (!sizes_supported(N, h, Vs)) return VP_ERR_UNSUPPORTED;
+    return dev(launch_embed_fwd(table_shard, ids, (int)N, (int)h, (int)Vs, shard_offset, dt == VP_BF16 ? 2 : 4, out,
+                                (hipStream_t)stream));
+}
+
+vp_status vp_embed_bwd(const void* grad_out, const int64_t* ids, int64_t N, int64_t h, int64_t Vs,
+                       int64_t shard_offset, vp_dtype dt, float* dtable_shard, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    if (!grad_out || !ids || !dtable_shard) return VP_ERR_INVALID_ARG;
+    if (!sizes_ok(N, h, Vs) || !dtype_ok(dt) || shard_offset < 0) return VP_ERR_INVALID_ARG;
+    if (!aligned16(grad_out) || !aligned16(dtable_shard) || !aligned16(workspace)) return VP_ERR_INVALID_ARG;
+    if (!sizes_supported(N, h, Vs) || N > ((int64_t)1 << 24)) return VP_ERR_UNSUPPORTED;
+    const size_t need = vp_workspace_bytes(VP_CALL_EMBED_BWD, N, h, Vs, dt, 0);
+    if (!workspace || workspace_bytes < need) return VP_ERR_WORKSPACE;
+    return dev(launch_embed_bwd(grad_out, ids, (int)N, (int)h, (int)Vs, shard_offset, dt == VP_BF16 ? 1 : 0,
+                                dtable_shard, workspace, (hipStream_t)stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,329 @@
+// bf16 x bf16 -> fp32 MFMA GEMM for gfx950 with the vocabulary-layer epilogues.
+//
+// One kernel template serves the three dense products of the output layer (section 4.2 of
+// the paper: Y = X W^T, dX = D W, dW = D^T X).  C[M,N] = A[M,K] * B[N,K]^T where each operand
+// is stored either with K contiguous ("kcontig", read from LDS with one 16-byte load per
+// MFMA operand) or with K strided (stored as [K][rows]).
+//
+// Work decomposition: 256x256 output tile per workgroup of 4 wavefronts (2x2), each
+// wavefront owns 128x128 = 4x4 tiles of the 32x32x16 bf16 MFMA (256 fp32 accumulators per
+// lane).  K advances in steps of 64 through two LDS stages; the global loads of step k+1 are
+// issued before the MFMAs of step k and written to the other stage afterwards.
+//
+// MFMA 32x32x16 operand layout (wave64): lane l supplies row (l % 32) of its operand and the
+// 8 consecutive k values starting at 8 * (l / 32); accumulator register r of lane l holds
+// C[8*(r/4) + 4*(l/32) + r%4][l % 32].
+#include "vp_internal.h"
+
+namespace vp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = GEMM_BM, BN = GEMM_BN, BK = 64;
+constexpr int NT = 256;                       // threads per workgroup
+constexpr int KC_ROW_BYTES = BK * 2;          // 128 B per row of a kcontig tile
+constexpr int KC_TILE_BYTES = 256 * KC_ROW_BYTES;           // 32 KB
+constexpr int KS_ROW_BYTES = 256 * 2 + 16;    // k-strided tile: [BK][256] bf16 + pad
+constexpr int KS_TILE_BYTES = BK * KS_ROW_BYTES;            // 33 KB
+constexpr int OPERAND_BYTES = KS_TILE_BYTES;  // slot size that fits either layout
+constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;
+constexpr int LDS_BYTES = 2 * STAGE_BYTES;    // two stages: ~132 KB of the 160 KB per CU
+
+// 16-byte chunk of 8 bf16 from a [rows][cols] row-major matrix at (row, col), zero-filled
+// outside the matrix.  vec_ok: rows start 16-byte aligned and col is a multiple of 8.
+__device__ __forceinline__ uint4 load_chunk(const u16* __restrict__ p, int row, int col, int rows, int cols,
+                                            int ld, int vec_ok) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (row < rows) {
+        const u16* q = p + (size_t)row * ld + col;
+        if (vec_ok && col + 8 <= cols) {
+            v = *reinterpret_cast<const uint4*>(q);
+        } else {
+            u16 e[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = (col + j < cols) ? q[j] : (u16)0;
+            v.x = e[0] | ((unsigned)e[1] << 16);
+            v.y = e[2] | ((unsigned)e[3] << 16);
+            v.z = e[4] | ((unsigned)e[5] << 16);
+            v.w = e[6] | ((unsigned)e[7] << 16);
+        }
+    }
+    return v;
+}
+
+// Global -> registers for one 256 x 64 operand tile (8 chunks of 16 B per thread).
+//  kcontig : matrix stored [R][K]; chunk q -> row q/8, k-chunk q%8 (8 lanes read 128 B of a row)
+//  kstrided: matrix stored [K][R]; chunk q -> k-row q/32, row-chunk q%32 (32 lanes read 512 B)
+template <bool KC>
+__device__ __forceinline__ void load_tile(uint4 (&r)[8], const u16* __restrict__ p, int r0, int k0, int R, int K,
+                                          int ld, int vec_ok, int tid) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int q = tid + NT * i;
+        if (KC) {
+            r[i] = load_chunk(p, r0 + (q >> 3), k0 + (q & 7) * 8, R, K, ld, vec_ok);
+        } else {
+            r[i] = load_chunk(p, k0 + (q >> 5), r0 + (q & 31) * 8, K, R, ld, vec_ok);
+        }
+    }
+}
+
+// Registers -> LDS.  kcontig tiles are [256][64] bf16 with the 16-byte chunk index XOR-ed
+// with (row & 7), which makes both these stores and the operand reads bank-conflict free.
+template <bool KC>
+__device__ __forceinline__ void store_tile(const uint4 (&r)[8], char* s, int tid) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int q = tid + NT * i;
+        if (KC) {
+            const int row = q >> 3, c = q & 7;
+            *reinterpret_cast<uint4*>(s + row * KC_ROW_BYTES + ((c ^ (row & 7)) << 4)) = r[i];
+        } else {
+            const int krow = q >> 5, c = q & 31;
+            *reinterpret_cast<uint4*>(s + krow * KS_ROW_BYTES + (c << 4)) = r[i];
+        }
+    }
+}
+
+// MFMA operand for tile row `row` (0..255 within the block tile), k sub-step kk (0..3), lane half hf.
+template <bool KC>
+__device__ __forceinline__ bf16x8 read_frag(const char* s, int row, int kk, int hf) {
+    if (KC) {
+        const int chunk = kk * 2 + hf;
+        return *reinterpret_cast<const bf16x8*>(s + row * KC_ROW_BYTES + ((chunk ^ (row & 7)) << 4));
+    } else {
+        union { u16 e[8]; bf16x8 v; } u;
+        const int kbase = kk * 16 + hf * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            u.e[j] = *reinterpret_cast<const u16*>(s + (kbase + j) * KS_ROW_BYTES + row * 2);
+        return u.v;
+    }
+}
+
+__device__ __forceinline__ float xor_max32(float v) {
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float xor_sum32(float v) {
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ u16 f32_to_bf16(float f) {
+    __bf16 b = (__bf16)f;   // round to nearest even
+    return __builtin_bit_cast(u16, b);
+}
+
+// Workgroup id -> output tile.  Workgroups are handed to the 8 XCDs round-robin, so ids
+// congruent mod 8 share an L2: give each XCD one contiguous run of logical tiles, and walk
+// the tiles in panels of 8 tile-rows, so the 32 workgroups resident on an XCD cover a
+// compact patch and re-use each other's operand panels from that L2.
+__device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int x = b & 7, per = nb >> 3, rem = nb & 7;
+    const int logical = x * per + (x < rem ? x : rem) + (b >> 3);
+    constexpr int GM = 8;
+    const int panel = logical / (GM * tiles_n);
+    const int first_m = panel * GM;
+    const int rows = (tiles_m - first_m < GM) ? (tiles_m - first_m) : GM;
+    const int in_panel = logical - panel * GM * tiles_n;
+    tm = first_m + in_panel % rows;
+    tn = in_panel / rows;
+}
+
+template <bool A_KC, bool B_KC, Epi EPI>
+__global__ __launch_bounds__(NT) void gemm_bf16_kernel(GemmBf16Params g) {
+    __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, hf = lane >> 5;
+
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    int tile_m, tile_n;
+    tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    uint4 ra[8], rb[8];
+    const int nkt = (g.K + BK - 1) / BK;
+
+    load_tile<A_KC>(ra, g.A, m0, 0, g.M, g.K, g.lda, g.vec_ok, tid);
+    load_tile<B_KC>(rb, g.B, n0, 0, g.N, g.K, g.ldb, g.vec_ok, tid);
+    store_tile<A_KC>(ra, smem, tid);
+    store_tile<B_KC>(rb, smem + OPERAND_BYTES, tid);
+    __syncthreads();
+
+    for (int kt = 0; kt < nkt; ++kt) {
+        const char* sA = smem + (kt & 1) * STAGE_BYTES;
+        const char* sB = sA + OPERAND_BYTES;
+        const bool more = (kt + 1 < nkt);
+        if (more) {
+            load_tile<A_KC>(ra, g.A, m0, (kt + 1) * BK, g.M, g.K, g.lda, g.vec_ok, tid);
+            load_tile<B_KC>(rb, g.B, n0, (kt + 1) * BK, g.N, g.K, g.ldb, g.vec_ok, tid);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 af[4], bfr[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) af[t] = read_frag<A_KC>(sA, wm * 128 + t * 32 + l32, kk, hf);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) bfr[t] = read_frag<B_KC>(sB, wn * 128 + t * 32 + l32, kk, hf);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            char* dA = smem + ((kt + 1) & 1) * STAGE_BYTES;
+            store_tile<A_KC>(ra, dA, tid);
+            store_tile<B_KC>(rb, dA + OPERAND_BYTES, tid);
+        }
+        __syncthreads();
+    }
+
+    // ---------------------------------------------------------------- epilogues
+    // element (i, j, r) of this lane: row = rbase + i*32 + 8*(r/4) + (r%4), col = cbase + j*32
+    const int rbase = m0 + wm * 128 + 4 * hf;
+    const int cbase = n0 + wn * 128 + l32;
+
+    if (EPI == Epi::StoreF32 || EPI == Epi::AccumF32) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
+                if (row < g.M) {
+                    float* crow = g.C + (size_t)row * g.ldc;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int col = cbase + j * 32;
+                        if (col < g.N) {
+                            if (EPI == Epi::AccumF32) crow[col] += acc[i][j][r];
+                            else crow[col] = acc[i][j][r];
+                        }
+                    }
+                }
+            }
+    }
+
+    if (EPI == Epi::DLogits) {
+        // D = (softmax - G) * scale with the global statistics (pass T of Algorithm 1, with
+        // the logits taken from the accumulators instead of memory)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
+                if (row < g.M) {
+                    const float m = g.gmax[row];
+                    const float inv = 1.0f / g.gsum[row];
+                    const int64_t lab = g.labels[row] - g.shard_offset;
+                    u16* drow = g.Y + (size_t)row * g.ldy;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int col = cbase + j * 32;
+                        if (col < g.N) {
+                            float d = __expf(acc[i][j][r] - m) * inv;
+                            if (lab == (int64_t)col) d -= 1.0f;
+                            drow[col] = f32_to_bf16(d * g.scale);
+                        }
+                    }
+                }
+            }
+    }
+
+    if (EPI == Epi::FwdStats) {
+        // shard-local m' and sum' of Algorithm 1's pass S, restricted to this tile's 256
+        // columns; the per-tile pairs are folded afterwards exactly like shards are (online
+        // softmax rescaling).  The LDS stages are free now and carry the 2-wave exchange.
+        float* xm = reinterpret_cast<float*>(smem);          // [2][256]
+        float* xs = xm + 512;                                  // [2][256]
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
+                float v = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (cbase + j * 32 < g.N) v = fmaxf(v, acc[i][j][r]);
+                const float m = xor_max32(v);
+                float s = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (cbase + j * 32 < g.N) s += __expf(acc[i][j][r] - m);
+                s = xor_sum32(s);
+                if (l32 == 0) {
+                    const int lr = row - m0;
+                    xm[wn * 256 + lr] = m;
+                    xs[wn * 256 + lr] = s;
+                }
+                if (row < g.M) {
+                    const int64_t lab = g.labels[row] - g.shard_offset;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int col = cbase + j * 32;
+                        if (lab == (int64_t)col && col < g.N) g.part_tgt[row] = acc[i][j][r];
+                    }
+                    if (g.Y) {
+                        u16* yrow = g.Y + (size_t)row * g.ldy;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int col = cbase + j * 32;
+                            if (col < g.N) yrow[col] = f32_to_bf16(acc[i][j][r]);
+                        }
+                    }
+                }
+            }
+        __syncthreads();
+        {
+            const int row = m0 + tid;
+            if (row < g.M) {
+                const float ma = xm[tid], mb = xm[256 + tid];
+                const float m = fmaxf(ma, mb);
+                float s = 0.f;
+                if (ma > -INFINITY) s += xs[tid] * __expf(ma - m);
+                if (mb > -INFINITY) s += xs[256 + tid] * __expf(mb - m);
+                g.part_max[(size_t)tile_n * g.M + row] = m;
+                g.part_sum[(size_t)tile_n * g.M + row] = s;
+            }
+        }
+    }
+}
+
+template <bool A_KC, bool B_KC, Epi EPI>
+static hipError_t launch_t(const GemmBf16Params& p, hipStream_t st) {
+    const int tiles = (int)(ceil_div(p.M, BM) * ceil_div(p.N, BN));
+    hipLaunchKernelGGL((gemm_bf16_kernel<A_KC, B_KC, EPI>), dim3(tiles), dim3(NT), 0, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st) {
+    if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
+    const int kid = p.epi == Epi::FwdStats ? K_GEMM_FWD_STATS
+                  : p.epi == Epi::DLogits  ? K_GEMM_DLOGITS
+                  : p.epi == Epi::AccumF32 ? K_GEMM_DH : K_GEMM_DW;
+    ProfScope prof(kid, st);
+    // only the operand-layout / epilogue combinations the output layer uses are instantiated
+    if (p.a_kcontig && p.b_kcontig && p.epi == Epi::FwdStats) return launch_t<true, true, Epi::FwdStats>(p, st);
+    if (p.a_kcontig && p.b_kcontig && p.epi == Epi::DLogits) return launch_t<true, true, Epi::DLogits>(p, st);
+    if (p.a_kcontig && !p.b_kcontig && p.epi == Epi::AccumF32) return launch_t<true, false, Epi::AccumF32>(p, st);
+    if (!p.a_kcontig && !p.b_kcontig && p.epi == Epi::StoreF32) return launch_t<false, false, Epi::StoreF32>(p, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace vp

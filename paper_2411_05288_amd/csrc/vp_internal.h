@@ -1,0 +1,105 @@
+// Internal declarations shared by the libvp translation units (host side only; device
+// code does not call across files).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "vp.h"
+
+namespace vp {
+
+typedef unsigned short u16;  // bf16 bit pattern
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Kernel ids for the optional per-kernel timing (names in vp_profile.hip, same order).
+enum KernelId : int {
+    K_GEMM_FWD_STATS = 0, K_GEMM_DLOGITS, K_GEMM_DH, K_GEMM_DW, K_FOLD, K_COMBINE, K_DLOGITS_EW, K_GEMM_F32,
+    K_ROWSTATS_F32, K_EMBED_FWD, K_EMBED_KEYS, K_EMBED_SORT, K_EMBED_ACCUM, K_COUNT
+};
+
+// Brackets the launches made during its lifetime with two events when timing is enabled;
+// does nothing (and touches no HIP API) otherwise.
+class ProfScope {
+public:
+    ProfScope(int id, hipStream_t st);
+    ~ProfScope();
+    ProfScope(const ProfScope&) = delete;
+    ProfScope& operator=(const ProfScope&) = delete;
+private:
+    int id_;
+    hipStream_t st_;
+    void* a_;
+};
+
+// Macro tile of the bf16 MFMA kernels (rows x cols of the output per workgroup).
+constexpr int GEMM_BM = 256;
+constexpr int GEMM_BN = 256;
+
+// What the bf16 GEMM does with its accumulators.
+enum class Epi : int {
+    FwdStats = 0,   // per-row partial max / sum-exp / target logit (+ optional bf16 store of Y)
+    DLogits = 1,    // D = (exp(Y - m)/sum - onehot) * scale, stored as bf16
+    StoreF32 = 2,   // C = acc
+    AccumF32 = 3    // C += acc
+};
+
+struct GemmBf16Params {
+    // operands: A is logically [M, K], B is logically [N, K]
+    const u16* A;
+    const u16* B;
+    int M, N, K;
+    int lda, ldb;        // leading dimension in elements of the matrices as stored
+    int a_kcontig;       // 1: A stored [M][K]; 0: stored [K][M]
+    int b_kcontig;       // 1: B stored [N][K]; 0: stored [K][N]
+    int vec_ok;          // 1: all rows of A and B start 16-byte aligned (16-byte loads allowed)
+    // epilogue
+    Epi epi;
+    float* C;            // StoreF32 / AccumF32: [M, N] fp32, ldc
+    int ldc;
+    u16* Y;              // FwdStats: optional bf16 [M, N] store (ldy); DLogits: D output
+    int ldy;
+    const int64_t* labels;   // [M]
+    int64_t shard_offset;
+    float* part_max;     // FwdStats: [tiles_n, M]
+    float* part_sum;     // FwdStats: [tiles_n, M]
+    float* part_tgt;     // FwdStats: [M], written only for rows whose label is in this shard
+    const float* gmax;   // DLogits: [M]
+    const float* gsum;   // DLogits: [M]
+    float scale;         // DLogits
+};
+
+hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st);
+
+// Generic strided fp32 GEMM: C[m,n] (+)= sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk]
+hipError_t launch_gemm_f32(const float* A, int64_t sam, int64_t sak,
+                           const float* B, int64_t sbn, int64_t sbk,
+                           float* C, int64_t ldc, int M, int N, int K, bool accumulate, hipStream_t st);
+
+// Row statistics of stored fp32 logits (fp32 path): m', sum', t'
+hipError_t launch_row_stats_f32(const float* Y, int64_t ldy, const int64_t* labels, int64_t off,
+                                int N, int Vs, float* lmax, float* lsum, float* ltgt, hipStream_t st);
+
+// Fold the per-column-tile partial statistics written by the FwdStats epilogue.
+hipError_t launch_fold_partials(const float* part_max, const float* part_sum, const float* part_tgt,
+                                int tiles, int N, const int64_t* labels, int64_t off, int Vs,
+                                float* lmax, float* lsum, float* ltgt, hipStream_t st);
+
+hipError_t launch_combine(const float* lmax, const float* lsum, const float* ltgt, int p, int N,
+                          float* gmax, float* gsum, float* loss_row, float* loss_mean, hipStream_t st);
+
+// D = (exp(Y - m)/sum - onehot) * scale from stored logits; is_bf16 selects the type of Y and D.
+hipError_t launch_dlogits(const void* Y, void* D, int is_bf16, const int64_t* labels, int64_t off,
+                          const float* gmax, const float* gsum, float scale, int N, int Vs, hipStream_t st);
+
+hipError_t launch_embed_fwd(const void* table, const int64_t* ids, int N, int h, int Vs, int64_t off,
+                            int elem_bytes, void* out, hipStream_t st);
+
+size_t embed_bwd_workspace(int64_t N);
+hipError_t launch_embed_bwd(const void* gout, const int64_t* ids, int N, int h, int Vs, int64_t off,
+                            int is_bf16, float* dtable, void* ws, hipStream_t st);
+
+}  // namespace vp

@@ -1,0 +1,86 @@
+// Optional per-kernel timing: when switched on, every kernel launch of the library is
+// bracketed by a pair of HIP events on the launch stream; vp_profile_read() sums the elapsed
+// times per kernel.  Off by default, in which case the library creates no events and keeps
+// no state.  This is a measurement aid for the benchmark, not part of the method.
+#include <mutex>
+#include <vector>
+
+#include "vp_internal.h"
+
+namespace vp {
+
+namespace {
+struct Rec { hipEvent_t a, b; int id; };
+std::mutex g_mu;
+bool g_on = false;
+std::vector<Rec> g_recs;
+std::vector<hipEvent_t> g_pool;
+
+hipEvent_t take_event() {
+    if (!g_pool.empty()) {
+        hipEvent_t e = g_pool.back();
+        g_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+ProfScope::ProfScope(int id, hipStream_t st) : id_(id), st_(st), a_(nullptr) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_on) return;
+    a_ = take_event();
+    if (a_) (void)hipEventRecord((hipEvent_t)a_, st_);
+}
+
+ProfScope::~ProfScope() {
+    if (!a_) return;
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipEvent_t b = take_event();
+    if (!b) { g_pool.push_back((hipEvent_t)a_); return; }
+    (void)hipEventRecord(b, st_);
+    g_recs.push_back(Rec{(hipEvent_t)a_, b, id_});
+}
+
+static const char* const kNames[K_COUNT] = {
+    "gemm_bf16_fwd_stats", "gemm_bf16_dlogits", "gemm_bf16_dH", "gemm_bf16_dW", "fold_partials",
+    "combine_stats", "dlogits_elementwise", "gemm_f32", "row_stats_f32", "embed_fwd",
+    "embed_bwd_keys", "embed_bwd_sort", "embed_bwd_accum"};
+
+}  // namespace vp
+
+extern "C" {
+
+int vp_profile_kernel_count(void) { return vp::K_COUNT; }
+
+const char* vp_profile_kernel_name(int id) { return (id >= 0 && id < vp::K_COUNT) ? vp::kNames[id] : ""; }
+
+vp_status vp_profile_enable(int on) {
+    std::lock_guard<std::mutex> lk(vp::g_mu);
+    vp::g_on = (on != 0);
+    return VP_OK;
+}
+
+vp_status vp_profile_read(double* ms_total, int64_t* launches, int n) {
+    if (!ms_total || !launches || n < vp::K_COUNT) return VP_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(vp::g_mu);
+    for (int i = 0; i < n; ++i) { ms_total[i] = 0.0; launches[i] = 0; }
+    vp_status rc = VP_OK;
+    for (const vp::Rec& r : vp::g_recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) {
+            rc = VP_ERR_DEVICE;
+        } else {
+            ms_total[r.id] += (double)ms;
+            launches[r.id] += 1;
+        }
+        vp::g_pool.push_back(r.a);
+        vp::g_pool.push_back(r.b);
+    }
+    vp::g_recs.clear();
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,192 @@
+// Small bandwidth/latency-bound kernels around the GEMMs: softmax statistics, their folds
+// (barrier C1 of Algorithm 1), and the D = softmax - G matrix of pass T from stored logits.
+#include "vp_internal.h"
+
+namespace vp {
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Block-wide reductions over 256 threads with a fixed tree (deterministic).
+__device__ __forceinline__ float block_max256(float v, float* sh) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+}
+__device__ __forceinline__ float block_sum256(float v, float* sh) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+// fp32 path, pass S statistics of one shard from its stored logits: one workgroup per row.
+__global__ __launch_bounds__(256) void row_stats_f32_kernel(const float* __restrict__ Y, int64_t ldy,
+                                                            const int64_t* __restrict__ labels, int64_t off,
+                                                            int Vs, float* lmax, float* lsum, float* ltgt) {
+    __shared__ float sh[4];
+    const int i = blockIdx.x;
+    const float* y = Y + (int64_t)i * ldy;
+    float m = -INFINITY;
+    for (int j = threadIdx.x; j < Vs; j += 256) m = fmaxf(m, y[j]);
+    m = block_max256(m, sh);
+    float s = 0.f;
+    for (int j = threadIdx.x; j < Vs; j += 256) s += expf(y[j] - m);
+    s = block_sum256(s, sh);
+    if (threadIdx.x == 0) {
+        lmax[i] = m;
+        lsum[i] = s;
+        const int64_t loc = labels[i] - off;
+        ltgt[i] = (loc >= 0 && loc < Vs) ? y[loc] : 0.f;
+    }
+}
+
+hipError_t launch_row_stats_f32(const float* Y, int64_t ldy, const int64_t* labels, int64_t off, int N, int Vs,
+                                float* lmax, float* lsum, float* ltgt, hipStream_t st) {
+    ProfScope prof(K_ROWSTATS_F32, st);
+    hipLaunchKernelGGL(row_stats_f32_kernel, dim3(N), dim3(256), 0, st, Y, ldy, labels, off, Vs, lmax, lsum, ltgt);
+    return hipGetLastError();
+}
+
+// Fold of the per-column-tile partial (max, sum-exp) pairs of one shard: the same online
+// rescaling as the cross-shard fold, in ascending tile order.
+__global__ __launch_bounds__(256) void fold_partials_kernel(const float* __restrict__ pm, const float* __restrict__ ps,
+                                                            const float* __restrict__ pt, int tiles, int N,
+                                                            const int64_t* __restrict__ labels, int64_t off, int Vs,
+                                                            float* lmax, float* lsum, float* ltgt) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= N) return;
+    float m = -INFINITY;
+    for (int t = 0; t < tiles; ++t) m = fmaxf(m, pm[(size_t)t * N + i]);
+    float s = 0.f;
+    for (int t = 0; t < tiles; ++t) s += ps[(size_t)t * N + i] * __expf(pm[(size_t)t * N + i] - m);
+    lmax[i] = m;
+    lsum[i] = s;
+    const int64_t loc = labels[i] - off;
+    ltgt[i] = (loc >= 0 && loc < Vs) ? pt[i] : 0.f;
+}
+
+hipError_t launch_fold_partials(const float* pm, const float* ps, const float* pt, int tiles, int N,
+                                const int64_t* labels, int64_t off, int Vs, float* lmax, float* lsum, float* ltgt,
+                                hipStream_t st) {
+    ProfScope prof(K_FOLD, st);
+    hipLaunchKernelGGL(fold_partials_kernel, dim3((unsigned)ceil_div(N, 256)), dim3(256), 0, st, pm, ps, pt, tiles, N,
+                       labels, off, Vs, lmax, lsum, ltgt);
+    return hipGetLastError();
+}
+
+// Barrier C1: global max, rescaled sum, per-row loss.  One thread per token row; the mean
+// loss is reduced by a second single-workgroup kernel with a fixed tree.
+__global__ __launch_bounds__(256) void combine_rows_kernel(const float* __restrict__ lmax, const float* __restrict__ lsum,
+                                                           const float* __restrict__ ltgt, int p, int N, float* gmax,
+                                                           float* gsum, float* loss_row) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= N) return;
+    float m = -INFINITY;
+    for (int r = 0; r < p; ++r) m = fmaxf(m, lmax[(size_t)r * N + i]);
+    float s = 0.f, t = 0.f;
+    for (int r = 0; r < p; ++r) {
+        s += lsum[(size_t)r * N + i] * expf(lmax[(size_t)r * N + i] - m);
+        t += ltgt[(size_t)r * N + i];
+    }
+    gmax[i] = m;
+    gsum[i] = s;
+    if (loss_row) loss_row[i] = m + logf(s) - t;
+}
+
+// Mean loss over the N rows by one workgroup: thread t sums rows t, t+256, ... in order, then
+// a fixed tree over the 256 threads.  Rows are recomputed from the global statistics so that
+// the per-row output stays optional.
+__global__ __launch_bounds__(256) void mean_loss_kernel(const float* __restrict__ gmax, const float* __restrict__ gsum,
+                                                        const float* __restrict__ ltgt, int p, int N, float* out) {
+    __shared__ float sh[4];
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < N; i += 256) {
+        float t = 0.f;
+        for (int r = 0; r < p; ++r) t += ltgt[(size_t)r * N + i];
+        acc += gmax[i] + logf(gsum[i]) - t;
+    }
+    acc = block_sum256(acc, sh);
+    if (threadIdx.x == 0) out[0] = acc / (float)N;
+}
+
+hipError_t launch_combine(const float* lmax, const float* lsum, const float* ltgt, int p, int N, float* gmax,
+                          float* gsum, float* loss_row, float* loss_mean, hipStream_t st) {
+    ProfScope prof(K_COMBINE, st);
+    hipLaunchKernelGGL(combine_rows_kernel, dim3((unsigned)ceil_div(N, 256)), dim3(256), 0, st, lmax, lsum, ltgt, p, N,
+                       gmax, gsum, loss_row);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(256), 0, st, gmax, gsum, ltgt, p, N, loss_mean);
+    return hipGetLastError();
+}
+
+// D = (exp(Y - m)/sum - G) * scale from stored logits (pass T of Algorithm 1 written with
+// the rescale identity of section 4.3 folded in: softmax' * sum' e^{m'-m} / sum = e^{Y-m}/sum).
+template <typename T>
+__device__ __forceinline__ float ld_as_f32(const T* p);
+template <>
+__device__ __forceinline__ float ld_as_f32<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float ld_as_f32<u16>(const u16* p) { return __uint_as_float((unsigned)(*p) << 16); }
+
+__device__ __forceinline__ void st_from_f32(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_from_f32(u16* p, float v) {
+    __bf16 b = (__bf16)v;
+    *p = __builtin_bit_cast(u16, b);
+}
+
+template <typename T, bool PRECISE>
+__global__ __launch_bounds__(256) void dlogits_kernel(const T* __restrict__ Y, T* __restrict__ D,
+                                                      const int64_t* __restrict__ labels, int64_t off,
+                                                      const float* __restrict__ gmax, const float* __restrict__ gsum,
+                                                      float scale, int Vs) {
+    const int i = blockIdx.y;
+    const float m = gmax[i];
+    const float inv = 1.0f / gsum[i];
+    const int64_t loc = labels[i] - off;
+    const T* y = Y + (int64_t)i * Vs;
+    T* d = D + (int64_t)i * Vs;
+    for (int j = blockIdx.x * 256 + threadIdx.x; j < Vs; j += gridDim.x * 256) {
+        const float v = ld_as_f32<T>(y + j) - m;
+        float pr = (PRECISE ? expf(v) : __expf(v)) * inv;
+        if ((int64_t)j == loc) pr -= 1.0f;
+        st_from_f32(d + j, pr * scale);
+    }
+}
+
+hipError_t launch_dlogits(const void* Y, void* D, int is_bf16, const int64_t* labels, int64_t off, const float* gmax,
+                          const float* gsum, float scale, int N, int Vs, hipStream_t st) {
+    ProfScope prof(K_DLOGITS_EW, st);
+    unsigned gx = (unsigned)ceil_div(Vs, 256);
+    if (gx > 64) gx = 64;
+    // grid.y carries the row; rows beyond 65535 are covered by launching in slabs
+    for (int r0 = 0; r0 < N; r0 += 65535) {
+        const int rows = (N - r0 < 65535) ? (N - r0) : 65535;
+        if (is_bf16) {
+            hipLaunchKernelGGL((dlogits_kernel<u16, false>), dim3(gx, rows), dim3(256), 0, st,
+                               (const u16*)Y + (int64_t)r0 * Vs, (u16*)D + (int64_t)r0 * Vs, labels + r0, off,
+                               gmax + r0, gsum + r0, scale, Vs);
+        } else {
+            hipLaunchKernelGGL((dlogits_kernel<float, true>), dim3(gx, rows), dim3(256), 0, st,
+                               (const float*)Y + (int64_t)r0 * Vs, (float*)D + (int64_t)r0 * Vs, labels + r0, off,
+                               gmax + r0, gsum + r0, scale, Vs);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace vp

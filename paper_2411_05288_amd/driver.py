@@ -1,0 +1,139 @@
+"""Host driver: runs the p shards of one configuration in sequence on one GPU.
+
+This is launch ordering and buffer ownership only.  It follows Algorithm 1 of the paper:
+pass S on every shard (vp_output_fwd), barrier C1 (vp_combine_stats, standing in for the two
+all-reduces), pass T on every shard (vp_output_bwd) with the reduce C2 realised as fp32
+accumulation into one dH buffer in ascending shard order.  All device buffers are allocated
+once, when the plan is built; a step allocates nothing.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class OutputLayerResult:
+    loss: torch.Tensor            # [1] fp32
+    loss_rows: torch.Tensor       # [N] fp32
+    global_max: torch.Tensor      # [N]
+    global_sumexp: torch.Tensor   # [N]
+    local_max: torch.Tensor       # [p, N]
+    local_sumexp: torch.Tensor    # [p, N]
+    local_target: torch.Tensor    # [p, N]
+    dH: torch.Tensor              # [N, h] fp32
+    dW: List[torch.Tensor]        # p x [Vs, h] fp32
+    logits: Optional[List[torch.Tensor]]
+
+
+class OutputLayerPlan:
+    """Buffers and launch order for one (N, h, Vs, p) output-layer workload."""
+
+    def __init__(self, H: torch.Tensor, W_shards: List[torch.Tensor], labels: torch.Tensor,
+                 save_logits: bool = True, grad_scale: Optional[float] = None):
+        self.H, self.W, self.labels = H, W_shards, labels
+        self.N, self.h = H.shape
+        self.p = len(W_shards)
+        self.Vs = W_shards[0].shape[0]
+        for w in W_shards:
+            if tuple(w.shape) != (self.Vs, self.h):
+                raise B.VPError("all shards must be [Vs, h]")
+        self.dt = B.VP_F32 if H.dtype == torch.float32 else B.VP_BF16
+        self.save_logits = save_logits
+        self.grad_scale = (1.0 / self.N) if grad_scale is None else float(grad_scale)
+        dev = H.device
+        f32 = dict(dtype=torch.float32, device=dev)
+        N, h, p, Vs = self.N, self.h, self.p, self.Vs
+        self.local_max = torch.empty((p, N), **f32)
+        self.local_sumexp = torch.empty((p, N), **f32)
+        self.local_target = torch.empty((p, N), **f32)
+        self.global_max = torch.empty((N,), **f32)
+        self.global_sumexp = torch.empty((N,), **f32)
+        self.loss_rows = torch.empty((N,), **f32)
+        self.loss = torch.empty((1,), **f32)
+        self.dH = torch.empty((N, h), **f32)
+        self.dW = [torch.empty((Vs, h), **f32) for _ in range(p)]
+        self.logits = [torch.empty((N, Vs), dtype=H.dtype, device=dev) for _ in range(p)] if save_logits else None
+        flags = B.VP_SAVE_LOGITS if save_logits else 0
+        nbytes = max(B.vp_workspace_bytes(B.VP_CALL_OUTPUT_FWD, N, h, Vs, self.dt, flags),
+                     B.vp_workspace_bytes(B.VP_CALL_OUTPUT_BWD, N, h, Vs, self.dt, flags), 256)
+        self.workspace = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+
+    def forward(self, stream=None) -> None:
+        for r in range(self.p):
+            B.vp_output_fwd(self.H, self.W[r], self.labels, r * self.Vs,
+                            self.local_max[r], self.local_sumexp[r], self.local_target[r],
+                            self.logits[r] if self.logits is not None else None, self.workspace, stream)
+        B.vp_combine_stats(self.local_max, self.local_sumexp, self.local_target,
+                           self.global_max, self.global_sumexp, self.loss_rows, self.loss, stream)
+
+    def backward(self, stream=None) -> None:
+        self.dH.zero_()
+        for r in range(self.p):
+            B.vp_output_bwd(self.H, self.W[r], self.labels, r * self.Vs, self.global_max, self.global_sumexp,
+                            self.logits[r] if self.logits is not None else None, self.grad_scale,
+                            self.dH, self.dW[r], self.workspace, stream)
+
+    def step(self, stream=None) -> None:
+        self.forward(stream)
+        self.backward(stream)
+
+    def result(self) -> OutputLayerResult:
+        return OutputLayerResult(self.loss, self.loss_rows, self.global_max, self.global_sumexp,
+                                 self.local_max, self.local_sumexp, self.local_target,
+                                 self.dH, self.dW, self.logits)
+
+
+def output_layer_step(H, W_shards, labels, save_logits=True, grad_scale=None) -> OutputLayerResult:
+    """One forward + backward of the sharded output layer; returns all outputs."""
+    plan = OutputLayerPlan(H, W_shards, labels, save_logits, grad_scale)
+    plan.step()
+    return plan.result()
+
+
+class EmbeddingPlan:
+    """Buffers and launch order for the sharded input layer (appendix C)."""
+
+    def __init__(self, table_shards: List[torch.Tensor], ids: torch.Tensor, grad_out: Optional[torch.Tensor]):
+        self.tables, self.ids, self.grad_out = table_shards, ids, grad_out
+        self.p = len(table_shards)
+        self.Vs, self.h = table_shards[0].shape
+        self.N = ids.shape[0]
+        dev = ids.device
+        self.dt = B.VP_F32 if table_shards[0].dtype == torch.float32 else B.VP_BF16
+        self.out = [torch.empty((self.N, self.h), dtype=table_shards[0].dtype, device=dev) for _ in range(self.p)]
+        self.dtable = [torch.zeros((self.Vs, self.h), dtype=torch.float32, device=dev) for _ in range(self.p)]
+        nbytes = max(B.vp_workspace_bytes(B.VP_CALL_EMBED_BWD, self.N, self.h, self.Vs, self.dt, 0), 256)
+        self.workspace = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+
+    def forward(self, stream=None) -> None:
+        for r in range(self.p):
+            B.vp_embed_fwd(self.tables[r], self.ids, r * self.Vs, self.out[r], stream)
+
+    def backward(self, stream=None) -> None:
+        for r in range(self.p):
+            B.vp_embed_bwd(self.grad_out, self.ids, r * self.Vs, self.dtable[r], self.workspace, stream)
+
+
+def embedding_forward(table_shards, ids):
+    plan = EmbeddingPlan(table_shards, ids, None)
+    plan.forward()
+    return plan.out
+
+
+def embedding_backward(grad_out, ids, Vs: int, p: int, dtable: Optional[List[torch.Tensor]] = None):
+    """Scatter-add into (optionally supplied, accumulate-into) fp32 shard gradients."""
+    N, h = grad_out.shape
+    dev = grad_out.device
+    if dtable is None:
+        dtable = [torch.zeros((Vs, h), dtype=torch.float32, device=dev) for _ in range(p)]
+    dt = B.VP_F32 if grad_out.dtype == torch.float32 else B.VP_BF16
+    nbytes = max(B.vp_workspace_bytes(B.VP_CALL_EMBED_BWD, N, h, Vs, dt, 0), 256)
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+    for r in range(p):
+        B.vp_embed_bwd(grad_out, ids, r * Vs, dtable[r], ws)
+    return dtable

@@ -1,0 +1,43 @@
+"""Helpers for the GPU parity tests: move seeded NumPy inputs to the GPU, run the HIP path
+through the C-ABI binding, bring results back as NumPy."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import synth_inputs as si
+
+
+def to_dev(x: np.ndarray) -> torch.Tensor:
+    """uint16 arrays are bf16 bit patterns; everything else keeps its dtype."""
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(x).cuda()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """Back to NumPy; bf16 comes back as uint16 bit patterns."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def to_host_f64(t: torch.Tensor) -> np.ndarray:
+    return si.as_f64(to_host(t))
+
+
+def run_output_layer(H, Ws, labels, save_logits=True, grad_scale=None):
+    import paper_2411_05288_amd as vp
+    plan = vp.driver.OutputLayerPlan(to_dev(H), [to_dev(w) for w in Ws], to_dev(labels), save_logits, grad_scale)
+    plan.step()
+    torch.cuda.synchronize()
+    return plan
+
+
+# tolerances of the parity bar
+LOSS_RTOL = 1e-3          # stated bar for the loss (the tests also report the achieved error)
+GRAD_TOL = {"bf16": 2e-2, "f32": 1e-5}   # max-abs error / max|tensor|
+
+
+def rel_max_err(got: np.ndarray, ref: np.ndarray) -> float:
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))

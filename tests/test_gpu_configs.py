@@ -1,0 +1,118 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times.  cfg2 is compared element by element with the full oracle.  cfg3 and cfg4 are
+too large for three fp64 products on the host: the oracle evaluates the row statistics over
+the whole vocabulary, and the definitions of dH / dW on sampled token rows and sampled
+vocabulary rows (every sampled output is computed exactly as the definition states)."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import vp_oracle as oc
+from gpu_util import GRAD_TOL, LOSS_RTOL, rel_max_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _build(cfg):
+    import paper_2411_05288_amd as vp
+    H = si.make_H(cfg)
+    labels = si.make_labels(cfg)
+    Ws = [si.make_W_shard(cfg, r) for r in range(cfg.p)]
+    plan = vp.driver.OutputLayerPlan(to_dev(H), [to_dev(w) for w in Ws], to_dev(labels), cfg.save_logits)
+    plan.step()
+    torch.cuda.synchronize()
+    return H, Ws, labels, plan
+
+
+@pytest.mark.timeout(600)
+def test_cfg2_llama_full_oracle():
+    cfg = si.CONFIGS["cfg2_llama"]
+    H, Ws, labels, plan = _build(cfg)
+    t0 = time.time()
+    X = si.as_f64(H)
+    W = np.concatenate([si.as_f64(w) for w in Ws])
+    ref = oc.output_layer(X, W, labels)
+    print("cfg2 oracle seconds", time.time() - t0, flush=True)
+    loss = float(to_host(plan.loss)[0])
+    assert abs(loss - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+    np.testing.assert_allclose(to_host(plan.global_max), ref["m"], rtol=0, atol=2e-3)
+    np.testing.assert_allclose(to_host(plan.global_sumexp), ref["sum"], rtol=2e-3)
+    np.testing.assert_allclose(to_host(plan.loss_rows), ref["loss_rows"], rtol=LOSS_RTOL, atol=2e-3)
+    e_dH = rel_max_err(to_host(plan.dH).astype(np.float64), ref["dX"])
+    dW = np.concatenate([to_host(w) for w in plan.dW]).astype(np.float64)
+    e_dW = rel_max_err(dW, ref["dW"])
+    print("cfg2 loss rel err %.3g dH err %.3g dW err %.3g" % (abs(loss - ref["loss"]) / ref["loss"], e_dH, e_dW),
+          flush=True)
+    assert e_dH <= GRAD_TOL["bf16"] and e_dW <= GRAD_TOL["bf16"]
+
+
+def _sampled_check(cfg, gemm_dtype, n_tok=48, n_voc=48):
+    H, Ws, labels, plan = _build(cfg)
+    N, Vs, p = cfg.N, cfg.Vs, cfg.p
+    X = si.as_f64(H)
+    rng = np.random.default_rng(12345)
+    tok = np.sort(rng.choice(N, n_tok, replace=False))
+    # include the vocabulary rows that carry the most labels (largest one-hot contribution)
+    hot = np.bincount(labels, minlength=cfg.V).argsort()[-8:]
+    voc = np.unique(np.concatenate([rng.choice(cfg.V, n_voc, replace=False), hot]))
+
+    # statistics of every token row over the whole vocabulary
+    t0 = time.time()
+    if gemm_dtype == np.float64:
+        st = oc.stats_streamed(X, (si.as_f64(w) for w in Ws), labels)
+    else:
+        # fp32 products for the rows that are not sampled; the sampled rows are redone in fp64
+        # below and the two are compared, so the fp32 shortcut is itself checked by the oracle
+        X32 = X.astype(np.float32)
+        st = oc.stats_streamed(X32, (si.as_f32(w) for w in Ws), labels)
+        st = {k: (v.astype(np.float64) if isinstance(v, np.ndarray) else v) for k, v in st.items()}
+    print("%s stats over all rows: %.1f s" % (cfg.name, time.time() - t0), flush=True)
+
+    # sampled token rows in fp64, exactly as the definition states
+    Xs = X[tok]
+    ex = oc.stats_streamed(Xs, (si.as_f64(w) for w in Ws), labels[tok])
+    np.testing.assert_allclose(st["m"][tok], ex["m"], rtol=0, atol=1e-4)
+    np.testing.assert_allclose(st["sum"][tok], ex["sum"], rtol=1e-4)
+
+    gm, gs = to_host(plan.global_max), to_host(plan.global_sumexp)
+    np.testing.assert_allclose(gm, st["m"], rtol=0, atol=2e-3)
+    np.testing.assert_allclose(gs, st["sum"], rtol=2e-3)
+    np.testing.assert_allclose(to_host(plan.loss_rows)[tok], ex["loss_rows"], rtol=LOSS_RTOL, atol=2e-3)
+    loss = float(to_host(plan.loss)[0])
+    assert abs(loss - st["loss"]) <= LOSS_RTOL * abs(st["loss"])
+
+    # dH rows: sum over shards of D_i W_r
+    dH_ref = np.zeros((len(tok), cfg.h))
+    for r in range(p):
+        D = oc.D_block(ex["Y"][r], ex["m"], ex["sum"], labels[tok], r * Vs, 1.0 / N)
+        dH_ref += D @ si.as_f64(Ws[r])
+    dH_got = to_host(plan.dH)[tok].astype(np.float64)
+    scale_dH = float(plan.dH.abs().max())
+    e_dH = np.abs(dH_got - dH_ref).max() / scale_dH
+    # dW rows: D[:, j]^T X for sampled vocabulary rows j
+    Y_cols = np.stack([np.asarray(st["Y"][j // Vs][:, j % Vs], dtype=np.float64) for j in voc], axis=1)
+    P = np.exp(Y_cols - st["m"][:, None]) / st["sum"][:, None]
+    G = (labels[:, None] == voc[None, :]).astype(np.float64)
+    dW_ref = ((P - G) / N).T @ X
+    dW_got = np.stack([to_host(plan.dW[j // Vs][j % Vs]) for j in voc]).astype(np.float64)
+    scale_dW = max(float(w.abs().max()) for w in plan.dW)
+    e_dW = np.abs(dW_got - dW_ref).max() / scale_dW
+    print("%s loss rel err %.3g dH err %.3g dW err %.3g" % (cfg.name, abs(loss - st["loss"]) / st["loss"], e_dH,
+                                                            e_dW), flush=True)
+    assert e_dH <= GRAD_TOL["bf16"] and e_dW <= GRAD_TOL["bf16"]
+    # properties that hold at any size: column sums of the full dW vanish (rows of D sum to 0)
+    colsum = sum(w.double().sum(dim=0) for w in plan.dW).cpu().numpy()
+    assert np.abs(colsum).max() <= 2e-2 * scale_dW * 4
+
+
+@pytest.mark.timeout(900)
+def test_cfg3_large_vocab_sampled():
+    _sampled_check(si.CONFIGS["cfg3_large_vocab"], np.float64)
+
+
+@pytest.mark.timeout(900)
+def test_cfg4_very_large_vocab_recompute_sampled():
+    _sampled_check(si.CONFIGS["cfg4_very_large_vocab"], np.float32)

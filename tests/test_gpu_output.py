@@ -1,0 +1,134 @@
+"""Parity of the HIP output-layer path (vp_output_fwd / vp_combine_stats / vp_output_bwd,
+called through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: loss within relative 1e-3; dH and dW within 2e-2 * max|tensor| for bf16 inputs and
+1e-5 * max|tensor| for fp32 inputs (max-abs error); statistics compared with tolerances
+derived from fp32 accumulation of K <= 8192 products (|dY| <~ 1e-4 at |Y| ~ 5)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import vp_oracle as oc
+from gpu_util import GRAD_TOL, LOSS_RTOL, rel_max_err, run_output_layer, to_dev, to_host, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def check_against_oracle(H, Ws, labels, save_logits, grad_scale=None, tag=""):
+    dtype = "bf16" if H.dtype == np.uint16 else "f32"
+    plan = run_output_layer(H, Ws, labels, save_logits, grad_scale)
+    X = si.as_f64(H)
+    W64 = [si.as_f64(w) for w in Ws]
+    ref = oc.output_layer_alg1(X, W64, labels, grad_scale)
+    full = oc.output_layer(X, np.concatenate(W64), labels, grad_scale)   # the unsharded definition
+
+    stat_atol = 2e-3 if dtype == "bf16" else 2e-5
+    stat_rtol = 2e-3 if dtype == "bf16" else 2e-5
+    np.testing.assert_allclose(to_host(plan.local_max), ref["m_loc"], rtol=0, atol=stat_atol, err_msg=tag)
+    np.testing.assert_allclose(to_host(plan.local_sumexp), ref["sum_loc"], rtol=stat_rtol, err_msg=tag)
+    np.testing.assert_allclose(to_host(plan.local_target), ref["t_loc"], rtol=0, atol=stat_atol, err_msg=tag)
+    np.testing.assert_allclose(to_host(plan.global_max), full["m"], rtol=0, atol=stat_atol, err_msg=tag)
+    np.testing.assert_allclose(to_host(plan.global_sumexp), full["sum"], rtol=stat_rtol, err_msg=tag)
+    np.testing.assert_allclose(to_host(plan.loss_rows), full["loss_rows"], rtol=LOSS_RTOL, atol=stat_atol, err_msg=tag)
+    loss = float(to_host(plan.loss)[0])
+    assert abs(loss - full["loss"]) <= LOSS_RTOL * abs(full["loss"]), tag
+    if save_logits:
+        for r in range(len(Ws)):
+            y = to_host_f64(plan.logits[r])
+            ytol = (2.0 ** -8) * np.abs(ref["Y"][r]).max() + 1e-6 if dtype == "bf16" else 2e-5
+            np.testing.assert_allclose(y, ref["Y"][r], rtol=0, atol=ytol, err_msg=tag)
+    tol = GRAD_TOL[dtype]
+    e_dH = rel_max_err(to_host(plan.dH).astype(np.float64), full["dX"])
+    assert e_dH <= tol, "%s dH err %g" % (tag, e_dH)
+    dW = np.concatenate([to_host(w).astype(np.float64) for w in plan.dW])
+    e_dW = rel_max_err(dW, full["dW"])
+    assert e_dW <= tol, "%s dW err %g" % (tag, e_dW)
+    for r in range(len(Ws)):     # every shard against Algorithm 1 run on the CPU
+        assert np.abs(to_host(plan.dW[r]) - ref["dW"][r]).max() <= tol * np.abs(full["dW"]).max(), tag
+    return {"loss_rel": abs(loss - full["loss"]) / abs(full["loss"]), "dH": e_dH, "dW": e_dW}
+
+
+# shapes chosen to span several 256x256 tiles with ragged tails in every dimension, a K that
+# is not a multiple of the 64-wide K step, and sizes that break 16-byte row alignment
+SMALL = [
+    # N,   h,   V,    p
+    (300, 136, 1040, 2),     # Vs = 520 = 2 tiles + 8 columns; K tail of 8
+    (257, 64, 792, 3),       # Vs = 264; N one row past a tile
+    (64, 200, 512, 1),       # single shard (textbook cross-entropy)
+    (513, 72, 500, 2),       # Vs = 250: rows of D not 16-byte aligned
+    (130, 100, 520, 2),      # h = 100: rows of H and W not 16-byte aligned
+    (1, 8, 8, 2),            # degenerate: one token, 4 vocabulary rows per shard
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("save_logits", [True, False])
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_cases_match_oracle(shape, save_logits, dtype):
+    N, h, V, p = shape
+    H, Ws, labels = si.small_output_case(N, h, V, p, dtype, seed=101 + N, w_std=0.08)
+    print("case", shape, save_logits, dtype, flush=True)
+    check_against_oracle(H, Ws, labels, save_logits, tag=str((shape, save_logits, dtype)))
+
+
+def test_cfg1_tiny_fp32():
+    cfg = si.CONFIGS["cfg1_tiny"]
+    H = si.make_H(cfg)
+    Ws = [si.make_W_shard(cfg, r) for r in range(cfg.p)]
+    labels = si.make_labels(cfg)
+    err = check_against_oracle(H, Ws, labels, cfg.save_logits, tag="cfg1")
+    print("cfg1 errors", err, flush=True)
+
+
+def test_unscaled_gradients_and_large_logits():
+    # grad_scale = 1 is the paper's unscaled form; W scaled so that |Y| reaches ~150,
+    # where an unshifted exp would overflow fp32
+    H, Ws, labels = si.small_output_case(96, 64, 768, 3, "f32", seed=5, w_std=5.0)
+    assert np.abs(si.as_f64(H) @ si.as_f64(np.concatenate(Ws)).T).max() > 100
+    check_against_oracle(H, Ws, labels, True, grad_scale=1.0, tag="large-logits f32")
+    H, Ws, labels = si.small_output_case(96, 64, 768, 3, "bf16", seed=5, w_std=2.0)
+    plan = run_output_layer(H, Ws, labels, False, 1.0)
+    assert np.isfinite(to_host(plan.dH)).all() and np.isfinite(to_host(plan.loss)).all()
+
+
+def test_labels_outside_every_shard_are_not_owned():
+    # ids outside [0, V) belong to no shard: target 0 on every shard, all-zero one-hot row
+    N, h, V, p = 70, 64, 512, 2
+    H, Ws, labels = si.small_output_case(N, h, V, p, "bf16", seed=9)
+    labels = labels.copy()
+    labels[::3] = V + 5
+    labels[1::7] = -3
+    plan = run_output_layer(H, Ws, labels, True)
+    X, W64 = si.as_f64(H), [si.as_f64(w) for w in Ws]
+    ref = oc.output_layer_alg1(X, W64, labels)       # the oracle's one_hot uses the same rule
+    np.testing.assert_allclose(to_host(plan.local_target), ref["t_loc"], atol=2e-3)
+    assert (to_host(plan.local_target)[:, ::3] == 0).all()
+    assert rel_max_err(to_host(plan.dH).astype(np.float64), ref["dX"]) <= 2e-2
+    dW = np.concatenate([to_host(w).astype(np.float64) for w in plan.dW])
+    assert rel_max_err(dW, np.concatenate(ref["dW"])) <= 2e-2
+
+
+def test_runs_are_bitwise_repeatable_and_dH_accumulates():
+    H, Ws, labels = si.small_output_case(300, 128, 1024, 2, "bf16", seed=77)
+    a = run_output_layer(H, Ws, labels, True)
+    b = run_output_layer(H, Ws, labels, True)
+    for x, y in [(a.dH, b.dH), (a.loss, b.loss), (a.local_sumexp, b.local_sumexp), (a.dW[1], b.dW[1])]:
+        assert torch.equal(x, y)
+    # dH_accum is accumulate-into: a second backward without zeroing doubles it
+    import paper_2411_05288_amd as vp
+    first = a.dH.clone()
+    for r in range(a.p):
+        vp.vp_output_bwd(a.H, a.W[r], a.labels, r * a.Vs, a.global_max, a.global_sumexp, a.logits[r],
+                         a.grad_scale, a.dH, a.dW[r], a.workspace)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_host(a.dH), 2 * to_host(first), rtol=1e-6, atol=1e-9)
+
+
+def test_stored_and_recomputed_logits_agree():
+    H, Ws, labels = si.small_output_case(260, 192, 1536, 2, "bf16", seed=31)
+    a = run_output_layer(H, Ws, labels, True)
+    b = run_output_layer(H, Ws, labels, False)
+    assert torch.equal(a.loss, b.loss)
+    # the stored path rounds Y to bf16 once more than the recomputing path
+    assert rel_max_err(to_host(a.dH).astype(np.float64), to_host(b.dH).astype(np.float64)) < 1e-2
