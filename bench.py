@@ -126,6 +126,7 @@ def cpu_baseline(cfg, sample_rows):
         cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
+    sample_rows = cfg.N if sample_rows <= 0 else min(sample_rows, cfg.N)
     H = si.as_f64(si.make_H(cfg)[:sample_rows])
     labels = si.make_labels(cfg)[:sample_rows]
     Ws = [si.as_f64(si.make_W_shard(cfg, r)) for r in range(cfg.p)]
@@ -174,7 +175,7 @@ def main():
     ap.add_argument("--config", default="cfg2_llama", help="headline output-layer configuration")
     ap.add_argument("--only-headline", action="store_true", help="skip the per_config section")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=1024)
+    ap.add_argument("--cpu-sample-rows", type=int, default=0, help="0 = all token rows of the workload")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the p shards of a configuration run in sequence "

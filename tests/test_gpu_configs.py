@@ -1,8 +1,9 @@
 """Parity at the full sizes of the benchmark configurations, in the launch configuration
 bench.py times.  cfg2 is compared element by element with the full oracle.  cfg3 and cfg4 are
-too large for three fp64 products on the host: the oracle evaluates the row statistics over
-the whole vocabulary, and the definitions of dH / dW on sampled token rows and sampled
-vocabulary rows (every sampled output is computed exactly as the definition states)."""
+large for three fp64 products and their [N, V] intermediates on the host: the oracle evaluates
+the logits and row statistics of every token over the whole vocabulary in fp64, and then the
+definitions of dH / dW on sampled token rows and sampled vocabulary rows (every sampled output
+is computed exactly as the definition states)."""
 import time
 
 import numpy as np
@@ -49,7 +50,7 @@ def test_cfg2_llama_full_oracle():
     assert e_dH <= GRAD_TOL["bf16"] and e_dW <= GRAD_TOL["bf16"]
 
 
-def _sampled_check(cfg, gemm_dtype, n_tok=48, n_voc=48):
+def _sampled_check(cfg, n_tok=48, n_voc=48):
     H, Ws, labels, plan = _build(cfg)
     N, Vs, p = cfg.N, cfg.Vs, cfg.p
     X = si.as_f64(H)
@@ -61,21 +62,12 @@ def _sampled_check(cfg, gemm_dtype, n_tok=48, n_voc=48):
 
     # statistics of every token row over the whole vocabulary
     t0 = time.time()
-    if gemm_dtype == np.float64:
-        st = oc.stats_streamed(X, (si.as_f64(w) for w in Ws), labels)
-    else:
-        # fp32 products for the rows that are not sampled; the sampled rows are redone in fp64
-        # below and the two are compared, so the fp32 shortcut is itself checked by the oracle
-        X32 = X.astype(np.float32)
-        st = oc.stats_streamed(X32, (si.as_f32(w) for w in Ws), labels)
-        st = {k: (v.astype(np.float64) if isinstance(v, np.ndarray) else v) for k, v in st.items()}
+    st = oc.stats_streamed(X, (si.as_f64(w) for w in Ws), labels)
     print("%s stats over all rows: %.1f s" % (cfg.name, time.time() - t0), flush=True)
 
-    # sampled token rows in fp64, exactly as the definition states
-    Xs = X[tok]
-    ex = oc.stats_streamed(Xs, (si.as_f64(w) for w in Ws), labels[tok])
-    np.testing.assert_allclose(st["m"][tok], ex["m"], rtol=0, atol=1e-4)
-    np.testing.assert_allclose(st["sum"][tok], ex["sum"], rtol=1e-4)
+    # the sampled token rows
+    ex = {"m": st["m"][tok], "sum": st["sum"][tok], "loss_rows": st["loss_rows"][tok],
+          "Y": [y[tok] for y in st["Y"]]}
 
     gm, gs = to_host(plan.global_max), to_host(plan.global_sumexp)
     np.testing.assert_allclose(gm, st["m"], rtol=0, atol=2e-3)
@@ -93,7 +85,7 @@ def _sampled_check(cfg, gemm_dtype, n_tok=48, n_voc=48):
     scale_dH = float(plan.dH.abs().max())
     e_dH = np.abs(dH_got - dH_ref).max() / scale_dH
     # dW rows: D[:, j]^T X for sampled vocabulary rows j
-    Y_cols = np.stack([np.asarray(st["Y"][j // Vs][:, j % Vs], dtype=np.float64) for j in voc], axis=1)
+    Y_cols = np.stack([st["Y"][j // Vs][:, j % Vs] for j in voc], axis=1)
     P = np.exp(Y_cols - st["m"][:, None]) / st["sum"][:, None]
     G = (labels[:, None] == voc[None, :]).astype(np.float64)
     dW_ref = ((P - G) / N).T @ X
@@ -110,9 +102,9 @@ def _sampled_check(cfg, gemm_dtype, n_tok=48, n_voc=48):
 
 @pytest.mark.timeout(900)
 def test_cfg3_large_vocab_sampled():
-    _sampled_check(si.CONFIGS["cfg3_large_vocab"], np.float64)
+    _sampled_check(si.CONFIGS["cfg3_large_vocab"])
 
 
 @pytest.mark.timeout(900)
 def test_cfg4_very_large_vocab_recompute_sampled():
-    _sampled_check(si.CONFIGS["cfg4_very_large_vocab"], np.float32)
+    _sampled_check(si.CONFIGS["cfg4_very_large_vocab"])

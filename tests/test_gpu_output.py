@@ -15,7 +15,7 @@ from gpu_util import GRAD_TOL, LOSS_RTOL, rel_max_err, run_output_layer, to_dev,
 pytestmark = pytest.mark.gpu
 
 
-def check_against_oracle(H, Ws, labels, save_logits, grad_scale=None, tag=""):
+def check_against_oracle(H, Ws, labels, save_logits, grad_scale=None, tag="", grad_tol=None):
     dtype = "bf16" if H.dtype == np.uint16 else "f32"
     plan = run_output_layer(H, Ws, labels, save_logits, grad_scale)
     X = si.as_f64(H)
@@ -23,8 +23,10 @@ def check_against_oracle(H, Ws, labels, save_logits, grad_scale=None, tag=""):
     ref = oc.output_layer_alg1(X, W64, labels, grad_scale)
     full = oc.output_layer(X, np.concatenate(W64), labels, grad_scale)   # the unsharded definition
 
-    stat_atol = 2e-3 if dtype == "bf16" else 2e-5
-    stat_rtol = 2e-3 if dtype == "bf16" else 2e-5
+    # absolute error of a logit grows with its magnitude (fp32 accumulation)
+    ymax = max(1.0, float(np.abs(full["Y"]).max()))
+    stat_atol = (2e-3 if dtype == "bf16" else 2e-6) * ymax
+    stat_rtol = 2e-3 if dtype == "bf16" else 2e-5 * ymax
     np.testing.assert_allclose(to_host(plan.local_max), ref["m_loc"], rtol=0, atol=stat_atol, err_msg=tag)
     np.testing.assert_allclose(to_host(plan.local_sumexp), ref["sum_loc"], rtol=stat_rtol, err_msg=tag)
     np.testing.assert_allclose(to_host(plan.local_target), ref["t_loc"], rtol=0, atol=stat_atol, err_msg=tag)
@@ -36,9 +38,9 @@ def check_against_oracle(H, Ws, labels, save_logits, grad_scale=None, tag=""):
     if save_logits:
         for r in range(len(Ws)):
             y = to_host_f64(plan.logits[r])
-            ytol = (2.0 ** -8) * np.abs(ref["Y"][r]).max() + 1e-6 if dtype == "bf16" else 2e-5
+            ytol = (2.0 ** -8) * np.abs(ref["Y"][r]).max() + 1e-6 if dtype == "bf16" else stat_atol
             np.testing.assert_allclose(y, ref["Y"][r], rtol=0, atol=ytol, err_msg=tag)
-    tol = GRAD_TOL[dtype]
+    tol = GRAD_TOL[dtype] if grad_tol is None else grad_tol
     e_dH = rel_max_err(to_host(plan.dH).astype(np.float64), full["dX"])
     assert e_dH <= tol, "%s dH err %g" % (tag, e_dH)
     dW = np.concatenate([to_host(w).astype(np.float64) for w in plan.dW])
@@ -86,7 +88,9 @@ def test_unscaled_gradients_and_large_logits():
     # where an unshifted exp would overflow fp32
     H, Ws, labels = si.small_output_case(96, 64, 768, 3, "f32", seed=5, w_std=5.0)
     assert np.abs(si.as_f64(H) @ si.as_f64(np.concatenate(Ws)).T).max() > 100
-    check_against_oracle(H, Ws, labels, True, grad_scale=1.0, tag="large-logits f32")
+    # one fp32 ulp of a logit of magnitude 150 is 1.5e-5 and enters exp() directly, so the
+    # 1e-5 bar of the benign configurations cannot hold here; 1e-4 bounds what fp32 allows
+    check_against_oracle(H, Ws, labels, True, grad_scale=1.0, tag="large-logits f32", grad_tol=1e-4)
     H, Ws, labels = si.small_output_case(96, 64, 768, 3, "bf16", seed=5, w_std=2.0)
     plan = run_output_layer(H, Ws, labels, False, 1.0)
     assert np.isfinite(to_host(plan.dH)).all() and np.isfinite(to_host(plan.loss)).all()
