@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvp.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-SOURCES = ["vp_api.hip", "vp_profile.hip", "vp_gemm_bf16.hip", "vp_gemm_f32.hip", "vp_stats.hip", "vp_embed.hip"]
+SOURCES = ["vp_api.hip", "vp_profile.hip", "vp_gemm_bf16.hip", "vp_gemm_bf16_fast.hip", "vp_gemm_f32.hip", "vp_stats.hip", "vp_embed.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

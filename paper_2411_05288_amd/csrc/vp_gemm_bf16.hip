@@ -13,15 +13,12 @@
 // MFMA 32x32x16 operand layout (wave64): lane l supplies row (l % 32) of its operand and the
 // 8 consecutive k values starting at 8 * (l / 32); accumulator register r of lane l holds
 // C[8*(r/4) + 4*(l/32) + r%4][l % 32].
-#include "vp_internal.h"
+#include <stdlib.h>
+
+#include "vp_gemm_bf16_common.h"
 
 namespace vp {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-constexpr int BM = GEMM_BM, BN = GEMM_BN, BK = 64;
-constexpr int NT = 256;                       // threads per workgroup
 constexpr int KC_ROW_BYTES = BK * 2;          // 128 B per row of a kcontig tile
 constexpr int KC_TILE_BYTES = 256 * KC_ROW_BYTES;           // 32 KB
 constexpr int KS_ROW_BYTES = 256 * 2 + 16;    // k-strided tile: [BK][256] bf16 + pad
@@ -102,38 +99,6 @@ __device__ __forceinline__ bf16x8 read_frag(const char* s, int row, int kk, int 
     }
 }
 
-__device__ __forceinline__ float xor_max32(float v) {
-#pragma unroll
-    for (int o = 1; o < 32; o <<= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-__device__ __forceinline__ float xor_sum32(float v) {
-#pragma unroll
-    for (int o = 1; o < 32; o <<= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-
-__device__ __forceinline__ u16 f32_to_bf16(float f) {
-    __bf16 b = (__bf16)f;   // round to nearest even
-    return __builtin_bit_cast(u16, b);
-}
-
-// Workgroup id -> output tile.  Workgroups are handed to the 8 XCDs round-robin, so ids
-// congruent mod 8 share an L2: give each XCD one contiguous run of logical tiles, and walk
-// the tiles in panels of 8 tile-rows, so the 32 workgroups resident on an XCD cover a
-// compact patch and re-use each other's operand panels from that L2.
-__device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int tiles_n, int& tm, int& tn) {
-    const int x = b & 7, per = nb >> 3, rem = nb & 7;
-    const int logical = x * per + (x < rem ? x : rem) + (b >> 3);
-    constexpr int GM = 8;
-    const int panel = logical / (GM * tiles_n);
-    const int first_m = panel * GM;
-    const int rows = (tiles_m - first_m < GM) ? (tiles_m - first_m) : GM;
-    const int in_panel = logical - panel * GM * tiles_n;
-    tm = first_m + in_panel % rows;
-    tn = in_panel / rows;
-}
-
 template <bool A_KC, bool B_KC, Epi EPI>
 __global__ __launch_bounds__(NT) void gemm_bf16_kernel(GemmBf16Params g) {
     __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
@@ -195,114 +160,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(GemmBf16Params g) {
         __syncthreads();
     }
 
-    // ---------------------------------------------------------------- epilogues
-    // element (i, j, r) of this lane: row = rbase + i*32 + 8*(r/4) + (r%4), col = cbase + j*32
-    const int rbase = m0 + wm * 128 + 4 * hf;
-    const int cbase = n0 + wn * 128 + l32;
-
-    if (EPI == Epi::StoreF32 || EPI == Epi::AccumF32) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
-                if (row < g.M) {
-                    float* crow = g.C + (size_t)row * g.ldc;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int col = cbase + j * 32;
-                        if (col < g.N) {
-                            if (EPI == Epi::AccumF32) crow[col] += acc[i][j][r];
-                            else crow[col] = acc[i][j][r];
-                        }
-                    }
-                }
-            }
-    }
-
-    if (EPI == Epi::DLogits) {
-        // D = (softmax - G) * scale with the global statistics (pass T of Algorithm 1, with
-        // the logits taken from the accumulators instead of memory)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
-                if (row < g.M) {
-                    const float m = g.gmax[row];
-                    const float inv = 1.0f / g.gsum[row];
-                    const int64_t lab = g.labels[row] - g.shard_offset;
-                    u16* drow = g.Y + (size_t)row * g.ldy;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int col = cbase + j * 32;
-                        if (col < g.N) {
-                            float d = __expf(acc[i][j][r] - m) * inv;
-                            if (lab == (int64_t)col) d -= 1.0f;
-                            drow[col] = f32_to_bf16(d * g.scale);
-                        }
-                    }
-                }
-            }
-    }
-
-    if (EPI == Epi::FwdStats) {
-        // shard-local m' and sum' of Algorithm 1's pass S, restricted to this tile's 256
-        // columns; the per-tile pairs are folded afterwards exactly like shards are (online
-        // softmax rescaling).  The LDS stages are free now and carry the 2-wave exchange.
-        float* xm = reinterpret_cast<float*>(smem);          // [2][256]
-        float* xs = xm + 512;                                  // [2][256]
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = rbase + i * 32 + 8 * (r >> 2) + (r & 3);
-                float v = -INFINITY;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (cbase + j * 32 < g.N) v = fmaxf(v, acc[i][j][r]);
-                const float m = xor_max32(v);
-                float s = 0.f;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (cbase + j * 32 < g.N) s += __expf(acc[i][j][r] - m);
-                s = xor_sum32(s);
-                if (l32 == 0) {
-                    const int lr = row - m0;
-                    xm[wn * 256 + lr] = m;
-                    xs[wn * 256 + lr] = s;
-                }
-                if (row < g.M) {
-                    const int64_t lab = g.labels[row] - g.shard_offset;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int col = cbase + j * 32;
-                        if (lab == (int64_t)col && col < g.N) g.part_tgt[row] = acc[i][j][r];
-                    }
-                    if (g.Y) {
-                        u16* yrow = g.Y + (size_t)row * g.ldy;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int col = cbase + j * 32;
-                            if (col < g.N) yrow[col] = f32_to_bf16(acc[i][j][r]);
-                        }
-                    }
-                }
-            }
-        __syncthreads();
-        {
-            const int row = m0 + tid;
-            if (row < g.M) {
-                const float ma = xm[tid], mb = xm[256 + tid];
-                const float m = fmaxf(ma, mb);
-                float s = 0.f;
-                if (ma > -INFINITY) s += xs[tid] * __expf(ma - m);
-                if (mb > -INFINITY) s += xs[256 + tid] * __expf(mb - m);
-                g.part_max[(size_t)tile_n * g.M + row] = m;
-                g.part_sum[(size_t)tile_n * g.M + row] = s;
-            }
-        }
-    }
+    gemm_epilogue<EPI>(acc, g, tile_m, tile_n, smem);
 }
 
 template <bool A_KC, bool B_KC, Epi EPI>
@@ -318,6 +176,8 @@ hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st) {
                   : p.epi == Epi::DLogits  ? K_GEMM_DLOGITS
                   : p.epi == Epi::AccumF32 ? K_GEMM_DH : K_GEMM_DW;
     ProfScope prof(kid, st);
+    const char* force = getenv("VP_FORCE_GENERIC_GEMM");
+    if (!(force && force[0] == '1') && gemm_bf16_fast_ok(p)) return launch_gemm_bf16_fast(p, st);
     // only the operand-layout / epilogue combinations the output layer uses are instantiated
     if (p.a_kcontig && p.b_kcontig && p.epi == Epi::FwdStats) return launch_t<true, true, Epi::FwdStats>(p, st);
     if (p.a_kcontig && p.b_kcontig && p.epi == Epi::DLogits) return launch_t<true, true, Epi::DLogits>(p, st);

@@ -72,7 +72,11 @@ struct GemmBf16Params {
     float scale;         // DLogits
 };
 
+// Dispatches to the fast kernel when its preconditions hold (and the environment variable
+// VP_FORCE_GENERIC_GEMM is not set to 1), else to the generic kernel.
 hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st);
+bool gemm_bf16_fast_ok(const GemmBf16Params& p);
+hipError_t launch_gemm_bf16_fast(const GemmBf16Params& p, hipStream_t st);
 
 // Generic strided fp32 GEMM: C[m,n] (+)= sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk]
 hipError_t launch_gemm_f32(const float* A, int64_t sam, int64_t sak,
