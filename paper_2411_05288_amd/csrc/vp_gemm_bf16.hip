@@ -11,8 +11,8 @@
 // issued before the MFMAs of step k and written to the other stage afterwards.
 //
 // MFMA 32x32x16 operand layout (wave64): lane l supplies row (l % 32) of its operand and the
-// 8 consecutive k values starting at 8 * (l / 32); accumulator register r of lane l holds
-// C[8*(r/4) + 4*(l/32) + r%4][l % 32].
+// 8 consecutive k values starting at 8 * (l / 32).  The accumulator layout and the epilogues
+// are shared with the fast kernel.
 #include <stdlib.h>
 
 #include "vp_gemm_bf16_common.h"
@@ -67,7 +67,7 @@ __device__ __forceinline__ void load_tile(uint4 (&r)[8], const u16* __restrict__
 }
 
 // Registers -> LDS.  kcontig tiles are [256][64] bf16 with the 16-byte chunk index XOR-ed
-// with (row & 7), which makes both these stores and the operand reads bank-conflict free.
+// with (row >> 1) & 7, which makes both these stores and the operand reads bank-conflict free.
 template <bool KC>
 __device__ __forceinline__ void store_tile(const uint4 (&r)[8], char* s, int tid) {
 #pragma unroll
@@ -75,7 +75,7 @@ __device__ __forceinline__ void store_tile(const uint4 (&r)[8], char* s, int tid
         const int q = tid + NT * i;
         if (KC) {
             const int row = q >> 3, c = q & 7;
-            *reinterpret_cast<uint4*>(s + row * KC_ROW_BYTES + ((c ^ (row & 7)) << 4)) = r[i];
+            *reinterpret_cast<uint4*>(s + row * KC_ROW_BYTES + ((c ^ ((row >> 1) & 7)) << 4)) = r[i];
         } else {
             const int krow = q >> 5, c = q & 31;
             *reinterpret_cast<uint4*>(s + krow * KS_ROW_BYTES + (c << 4)) = r[i];
@@ -88,7 +88,7 @@ template <bool KC>
 __device__ __forceinline__ bf16x8 read_frag(const char* s, int row, int kk, int hf) {
     if (KC) {
         const int chunk = kk * 2 + hf;
-        return *reinterpret_cast<const bf16x8*>(s + row * KC_ROW_BYTES + ((chunk ^ (row & 7)) << 4));
+        return *reinterpret_cast<const bf16x8*>(s + row * KC_ROW_BYTES + ((chunk ^ ((row >> 1) & 7)) << 4));
     } else {
         union { u16 e[8]; bf16x8 v; } u;
         const int kbase = kk * 16 + hf * 8;
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(GemmBf16Params g) {
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    mfma_tile(acc[i][j], af[i], bfr[j]);
         }
         if (more) {
             char* dA = smem + ((kt + 1) & 1) * STAGE_BYTES;

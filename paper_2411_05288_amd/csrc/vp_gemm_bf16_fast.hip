@@ -20,7 +20,9 @@
 // writes lane i's 16 bytes at byte 16*i of its 1 KB slot, so the swizzles below are applied to
 // the global address each lane fetches):
 //   K-contiguous tile  [256 rows][64 k]: 128 B rows; 16-byte chunk c of row r sits at chunk
-//       position c ^ (r & 7).  One ds_read_b128 per MFMA operand, conflict free.
+//       position c ^ ((r >> 1) & 7).  One ds_read_b128 per MFMA operand.  The LDS serves a
+//       ds_read_b128 in passes of 16 lanes over 64 banks, and the lanes of a pass are not
+//       consecutive (measured: XOR with r & 7 costs 1.67x, XOR with (r >> 1) & 7 is conflict free).
 //   K-strided tile [64 k][256 rows]: 512 B k-rows of 16 segments of 32 B (16 rows); segment s of
 //       k-row k sits at segment position s ^ f(k & 3), f = {0,5,2,7}.  MFMA operands are read
 //       with the transposing LDS load (ds_read_b64_tr_b16): in a group of 16 lanes, lane s
@@ -50,8 +52,8 @@ __device__ __forceinline__ void tile_voffsets(unsigned (&voff)[8], int r0, int l
     for (int jj = 0; jj < 8; ++jj) {
         const int slot = wave * 8 + jj;
         if (KC) {
-            const int row = slot * 8 + (lane >> 3);          // row & 7 == lane >> 3
-            const int c = (lane & 7) ^ (lane >> 3);
+            const int row = slot * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ ((row >> 1) & 7);
             voff[jj] = ((unsigned)(r0 + row) * (unsigned)ld + (unsigned)(c * 8)) * 2u;
         } else {
             const int krow = slot * 2 + (lane >> 5);
@@ -63,22 +65,37 @@ __device__ __forceinline__ void tile_voffsets(unsigned (&voff)[8], int r0, int l
     }
 }
 
-// The k advance is applied to the descriptor (base += kadv, size -= kadv) rather than to the
-// per-lane offsets: the offsets stay loop invariant, the advance costs two scalar ops, and the
-// range check still sees the true distance to the end of the operand.
-__device__ __forceinline__ void issue_tile_loads(const u16* base, unsigned bytes, unsigned kadv,
-                                                 const unsigned (&voff)[8], char* tile, int wave) {
-    const __amdgpu_buffer_rsrc_t rs =
-        __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + kadv), 0, (int)(bytes - kadv), 0x00020000);
+// Loads LO..HI-1 of the 16 wave-wide loads that bring one k tile into a stage (0..7: this
+// wavefront's 1 KB slots of the A tile, 8..15: of the B tile).  The k advance is applied to the
+// descriptor (base += kadv, size -= kadv) rather than to the per-lane offsets: the offsets stay
+// loop invariant, the advance costs a few scalar ops, and the range check still sees the true
+// distance to the end of the operand.  The advance is clamped to the operand size, so a tile
+// index past the end of K yields an empty descriptor (every lane reads zero, no access is made):
+// the main loop may therefore request tiles beyond K without a branch.
+template <int LO, int HI>
+__device__ __forceinline__ void issue_loads(const GemmBf16Params& g, unsigned a_bytes, unsigned b_bytes,
+                                            unsigned a_kadv, unsigned b_kadv, const unsigned (&avoff)[8],
+                                            const unsigned (&bvoff)[8], char* stage, int wave) {
+    a_kadv = a_kadv < a_bytes ? a_kadv : a_bytes;
+    b_kadv = b_kadv < b_bytes ? b_kadv : b_bytes;
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)g.A + a_kadv), 0,
+                                                                         (int)(a_bytes - a_kadv), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)g.B + b_kadv), 0,
+                                                                         (int)(b_bytes - b_kadv), 0x00020000);
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(tile + (wave * 8 + jj) * 1024), 16, (int)voff[jj], 0, 0,
-                                                 0);
+    for (int idx = LO; idx < HI; ++idx) {
+        if (idx < 8) {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr)(stage + (wave * 8 + idx) * 1024), 16,
+                                                     (int)avoff[idx], 0, 0, 0);
+        } else {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr)(stage + TILE_BYTES + (wave * 8 + idx - 8) * 1024),
+                                                     16, (int)bvoff[idx - 8], 0, 0, 0);
+        }
     }
 }
 
 // Per-lane LDS byte offsets for operand reads of the wavefront's 128 rows (4 MFMA tiles).
-//  KC: base[kk] = address of (row = wt*128 + l32, chunk (2kk + hf) ^ (l32 & 7)); tile t adds t*4096
+//  KC: base[kk] = address of (row = wt*128 + l32, chunk (2kk + hf) ^ ((l32 >> 1) & 7)); tile t adds t*4096
 //  KS: base[t]  = address of (k = 8*(b>>1) + s/4, segment of tile t and lane group b, 8*(s&3));
 //                 sub-step kk / half rd adds (16kk + 4rd) * 512
 template <bool KC>
@@ -87,7 +104,7 @@ __device__ __forceinline__ void frag_offsets(int (&base)[4], int wt, int lane) {
         const int l32 = lane & 31, hf = lane >> 5;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-            base[kk] = (wt * 128 + l32) * 128 + ((((kk << 1) | hf) ^ (l32 & 7)) << 4);
+            base[kk] = (wt * 128 + l32) * 128 + ((((kk << 1) | hf) ^ ((l32 >> 1) & 7)) << 4);
     } else {
         const int b = lane >> 4, s = lane & 15;
         const int f = seg_swizzle(s >> 2);
@@ -126,11 +143,40 @@ __device__ __forceinline__ void mfma_step(floatx16 (&acc)[4][4], const bf16x8 (&
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+            mfma_tile(acc[i][j], af[i], bf[j]);
 }
 
 template <bool A_KC, bool B_KC, Epi EPI>
 __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS bases in SGPRs
+    const int wm = wave >> 1, wn = wave & 1;
+
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const int total_tiles = tiles_m * tiles_n;
+
+    // raw buffer descriptors sized exactly to the operands: reads beyond return zero
+    const unsigned a_bytes = (unsigned)(A_KC ? g.M : g.K) * (unsigned)g.lda * 2u;
+    const unsigned b_bytes = (unsigned)(B_KC ? g.N : g.K) * (unsigned)g.ldb * 2u;
+    const unsigned a_kstep = A_KC ? (unsigned)BK * 2u : (unsigned)BK * (unsigned)g.lda * 2u;
+    const unsigned b_kstep = B_KC ? (unsigned)BK * 2u : (unsigned)BK * (unsigned)g.ldb * 2u;
+
+    int abase[4], bbase[4];
+    frag_offsets<A_KC>(abase, wm, lane);
+    frag_offsets<B_KC>(bbase, wn, lane);
+
+    // Persistent workgroups: one per compute unit, each walking the tile list with stride
+    // gridDim.x.  The stores of a tile's epilogue are fire-and-forget, so they drain while the
+    // next tile's operands are already streaming in.  Virtual id v keeps the XCD-aware tile
+    // order: v % 8 is the XCD of this workgroup for every tile it processes.
+    for (int v = blockIdx.x; v < total_tiles; v += gridDim.x) {
+    int tile_m, tile_n;
+    tile_of_block(v, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    // accumulators are zeroed directly in the AGPR half of the register file: zeroing them as
+    // ordinary vectors first would need 256 more VGPRs for a moment and spill everything else
     floatx16 acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -139,80 +185,130 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) { float z; asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(z)); acc[i][j][r] = z; }
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS bases in SGPRs
-    const int wm = wave >> 1, wn = wave & 1;
-
-    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-    int tile_m, tile_n;
-    tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    // raw buffer descriptors sized exactly to the operands: reads beyond return zero
-    const unsigned a_bytes = (unsigned)(A_KC ? g.M : g.K) * (unsigned)g.lda * 2u;
-    const unsigned b_bytes = (unsigned)(B_KC ? g.N : g.K) * (unsigned)g.ldb * 2u;
-    const unsigned a_kstep = A_KC ? (unsigned)BK * 2u : (unsigned)BK * (unsigned)g.lda * 2u;
-    const unsigned b_kstep = B_KC ? (unsigned)BK * 2u : (unsigned)BK * (unsigned)g.ldb * 2u;
-
     unsigned avoff[8], bvoff[8];
     tile_voffsets<A_KC>(avoff, m0, g.lda, wave, lane);
     tile_voffsets<B_KC>(bvoff, n0, g.ldb, wave, lane);
-    int abase[4], bbase[4];
-    frag_offsets<A_KC>(abase, wm, lane);
-    frag_offsets<B_KC>(bbase, wn, lane);
 
     const int nkt = (g.K + BK - 1) / BK;
 
-    // prologue: tile 0 -> stage 0, wait, then tile 1 -> stage 1 in flight
-    issue_tile_loads(g.A, a_bytes, 0u, avoff, g_stage0, wave);
-    issue_tile_loads(g.B, b_bytes, 0u, bvoff, g_stage0 + TILE_BYTES, wave);
+    // Instruction-mix hints for the scheduler: the next N MFMAs, LDS reads, global loads.
+#define VP_SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
+#define VP_SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
+#define VP_SCHED_VMEM(n) __builtin_amdgcn_sched_group_barrier(0x020, n, 0)
+    constexpr int DS_PER_STEP = (A_KC ? 4 : 8) + (B_KC ? 4 : 8);   // LDS reads per 16-wide k sub-step
+
+    // prologue: tile 0 -> stage 0 completely, then the first part of tile 1 -> stage 1
+    issue_loads<0, 16>(g, a_bytes, b_bytes, 0u, 0u, avoff, bvoff, g_stage0, wave);
     __syncthreads();
-    if (nkt > 1) {
-        issue_tile_loads(g.A, a_bytes, a_kstep, avoff, g_stage1, wave);
-        issue_tile_loads(g.B, b_bytes, b_kstep, bvoff, g_stage1 + TILE_BYTES, wave);
-    }
+    issue_loads<0, 6>(g, a_bytes, b_bytes, a_kstep, b_kstep, avoff, bvoff, g_stage1, wave);
     bf16x8 af0[4], bf0[4], af1[4], bf1[4];
     read_frags<A_KC, B_KC>(af0, bf0, g_stage0, abase, bbase, 0);
 
-    // One 64-wide k step on stage `cur` while tile kt+1 lands in `nxt`.  Entry: sub-step 0 operands
-    // of tile kt in (af0, bf0).  The barrier sits before the last sub-step's MFMAs: by then every
-    // wavefront has read all it needs from `cur`, so tile kt+2 can start streaming into it, and the
-    // first operands of tile kt+1 are fetched while the last MFMAs run.
-#define VP_K_STEP(cur, nxt, kt)                                                                     \
-    {                                                                                               \
-        read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 1);                                      \
-        mfma_step(acc, af0, bf0);                                                                   \
-        read_frags<A_KC, B_KC>(af0, bf0, cur, abase, bbase, 2);                                      \
-        mfma_step(acc, af1, bf1);                                                                   \
-        read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 3);                                      \
-        mfma_step(acc, af0, bf0);                                                                   \
-        __syncthreads();                                                                            \
-        if ((kt) + 2 < nkt) {                                                                       \
-            issue_tile_loads(g.A, a_bytes, (unsigned)((kt) + 2) * a_kstep, avoff, cur, wave);           \
-            issue_tile_loads(g.B, b_bytes, (unsigned)((kt) + 2) * b_kstep, bvoff, cur + TILE_BYTES, wave); \
-        }                                                                                           \
-        if ((kt) + 1 < nkt) read_frags<A_KC, B_KC>(af0, bf0, nxt, abase, bbase, 0);                  \
-        mfma_step(acc, af1, bf1);                                                                   \
+    // The k loop alternates two regions per 64-wide k tile T held in stage `cur`:
+    //  region 1: sub-steps 0..2 of tile T.  The loads 6..15 of tile T+1 (towards `nxt`) are spread
+    //            over the first two sub-steps, one every few MFMAs, so that no wavefront sits in
+    //            the (in-order) issue of a burst of global loads while its MFMA pipe runs dry.
+    //            It ends with the only barrier of the tile: tile T+1 has landed, and every
+    //            wavefront has fetched its last operands from `cur`.
+    //  region 2: sub-step 3 of tile T, during which the first operands of tile T+1 are fetched
+    //            from `nxt` and the first six loads of tile T+2 start streaming into `cur`.
+    // Loads past the end of K hit an empty descriptor and cost nothing.  The loop's back edge
+    // sits right after a barrier, where no load is in flight.
+#define VP_REGION1(cur, nxt, T)                                                                          \
+    {                                                                                                    \
+        read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 1);                                           \
+        issue_loads<6, 11>(g, a_bytes, b_bytes, (unsigned)((T) + 1) * a_kstep, (unsigned)((T) + 1) * b_kstep, \
+                           avoff, bvoff, nxt, wave);                                                      \
+        mfma_step(acc, af0, bf0);                                                                        \
+        _Pragma("unroll") for (int q = 0; q < 5; ++q) {                                                   \
+            VP_SCHED_MFMA(3);                                                                            \
+            VP_SCHED_DSRD((DS_PER_STEP + 4) / 5);                                                        \
+            VP_SCHED_VMEM(1);                                                                            \
+        }                                                                                                \
+        VP_SCHED_MFMA(1);                                                                                \
+        read_frags<A_KC, B_KC>(af0, bf0, cur, abase, bbase, 2);                                           \
+        issue_loads<11, 16>(g, a_bytes, b_bytes, (unsigned)((T) + 1) * a_kstep,                           \
+                            (unsigned)((T) + 1) * b_kstep, avoff, bvoff, nxt, wave);                      \
+        mfma_step(acc, af1, bf1);                                                                        \
+        _Pragma("unroll") for (int q = 0; q < 5; ++q) {                                                   \
+            VP_SCHED_MFMA(3);                                                                            \
+            VP_SCHED_DSRD((DS_PER_STEP + 4) / 5);                                                        \
+            VP_SCHED_VMEM(1);                                                                            \
+        }                                                                                                \
+        VP_SCHED_MFMA(1);                                                                                \
+        read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 3);                                           \
+        mfma_step(acc, af0, bf0);                                                                        \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
+            VP_SCHED_MFMA(4);                                                                            \
+            VP_SCHED_DSRD((DS_PER_STEP + 3) / 4);                                                        \
+        }                                                                                                \
+        __syncthreads();                                                                                 \
+    }
+#define VP_REGION2(cur, nxt, T)                                                                          \
+    {                                                                                                    \
+        read_frags<A_KC, B_KC>(af0, bf0, nxt, abase, bbase, 0);                                           \
+        issue_loads<0, 6>(g, a_bytes, b_bytes, (unsigned)((T) + 2) * a_kstep, (unsigned)((T) + 2) * b_kstep, \
+                          avoff, bvoff, cur, wave);                                                       \
+        mfma_step(acc, af1, bf1);                                                                        \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
+            VP_SCHED_MFMA(3);                                                                            \
+            VP_SCHED_DSRD((DS_PER_STEP + 5) / 6);                                                        \
+            VP_SCHED_VMEM(1);                                                                            \
+        }                                                                                                \
+        _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                                   \
+            VP_SCHED_MFMA(2);                                                                            \
+            VP_SCHED_DSRD((DS_PER_STEP + 5) / 6);                                                        \
+            VP_SCHED_VMEM(1);                                                                            \
+        }                                                                                                \
     }
 
-    for (int kt = 0; kt < nkt; kt += 2) {
-        VP_K_STEP(g_stage0, g_stage1, kt)
-        if (kt + 1 < nkt) VP_K_STEP(g_stage1, g_stage0, kt + 1)
+    VP_REGION1(g_stage0, g_stage1, 0)
+    int kt = 0;
+    for (; kt + 2 < nkt; kt += 2) {
+        VP_REGION2(g_stage0, g_stage1, kt)
+        VP_REGION1(g_stage1, g_stage0, kt + 1)
+        VP_REGION2(g_stage1, g_stage0, kt + 1)
+        VP_REGION1(g_stage0, g_stage1, kt + 2)
     }
-#undef VP_K_STEP
+    // tile kt sits in stage 0 with region 1 done; at most one more tile follows
+    VP_REGION2(g_stage0, g_stage1, kt)
+    if (kt + 1 < nkt) {
+        VP_REGION1(g_stage1, g_stage0, kt + 1)
+        VP_REGION2(g_stage1, g_stage0, kt + 1)
+    }
+#undef VP_REGION1
+#undef VP_REGION2
+#undef VP_SCHED_MFMA
+#undef VP_SCHED_DSRD
+#undef VP_SCHED_VMEM
     __syncthreads();   // every wavefront is done with the stages before the epilogue reuses them
 
     // keep the epilogue's address arithmetic from being hoisted above the main loop, where it
     // would occupy registers (and spill) for the whole kernel
     asm volatile("" : "+s"(tile_m), "+s"(tile_n));
     gemm_epilogue<EPI>(acc, g, tile_m, tile_n, g_stage0);
+    __syncthreads();   // the epilogue's LDS exchange is over before the next tile streams in
+    }   // persistent tile loop
+}
+
+// Compute units of the current device (one persistent workgroup each); queried once per device.
+static int compute_unit_count() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
 }
 
 template <bool A_KC, bool B_KC, Epi EPI>
 static hipError_t launch_fast_t(const GemmBf16Params& p, hipStream_t st) {
     const int tiles = (int)(ceil_div(p.M, BM) * ceil_div(p.N, BN));
-    hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI>), dim3(tiles), dim3(NT), 0, st, p);
+    const int cus = compute_unit_count();
+    hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI>), dim3(tiles < cus ? tiles : cus), dim3(NT), 0, st, p);
     return hipGetLastError();
 }
 

@@ -136,3 +136,11 @@ def test_stored_and_recomputed_logits_agree():
     assert torch.equal(a.loss, b.loss)
     # the stored path rounds Y to bf16 once more than the recomputing path
     assert rel_max_err(to_host(a.dH).astype(np.float64), to_host(b.dH).astype(np.float64)) < 1e-2
+
+
+def test_generic_gemm_kernel_on_aligned_shapes(monkeypatch):
+    # aligned shapes normally take the fast kernel; the generic one must give the same answers
+    monkeypatch.setenv("VP_FORCE_GENERIC_GEMM", "1")
+    H, Ws, labels = si.small_output_case(300, 128, 1040, 2, "bf16", seed=3, w_std=0.08)
+    check_against_oracle(H, Ws, labels, True, tag="generic kernel, stored logits")
+    check_against_oracle(H, Ws, labels, False, tag="generic kernel, recompute")
