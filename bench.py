@@ -175,6 +175,9 @@ def main():
     ap.add_argument("--config", default="cfg2_llama", help="headline output-layer configuration")
     ap.add_argument("--only-headline", action="store_true", help="skip the per_config section")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise copy of 256 MiB (read 256 MiB, write 256 MiB) five times, so "
+                         "that a counter run of this command carries a kernel of known HBM traffic")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="0 = all token rows of the workload")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -191,6 +194,13 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     cfg = si.CONFIGS[args.config]
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     plan = make_output_plan(vp, cfg, seeded_numpy=True)
     wall_ms, ev_ms = time_steps(plan.step, args.steps, args.warmup)
