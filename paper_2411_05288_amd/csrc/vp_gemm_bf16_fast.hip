@@ -238,10 +238,11 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
         VP_SCHED_MFMA(1);                                                                                \
         read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 3);                                           \
         mfma_step(acc, af0, bf0);                                                                        \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
-            VP_SCHED_MFMA(4);                                                                            \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {   /* operand reads early: they must have */     \
+            VP_SCHED_MFMA(1);                               /* landed when the barrier is reached  */     \
             VP_SCHED_DSRD((DS_PER_STEP + 3) / 4);                                                        \
         }                                                                                                \
+        VP_SCHED_MFMA(12);                                                                               \
         __syncthreads();                                                                                 \
     }
 #define VP_REGION2(cur, nxt, T)                                                                          \

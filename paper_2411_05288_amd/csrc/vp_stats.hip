@@ -105,20 +105,26 @@ __global__ __launch_bounds__(256) void combine_rows_kernel(const float* __restri
     if (loss_row) loss_row[i] = m + logf(s) - t;
 }
 
-// Mean loss over the N rows by one workgroup: thread t sums rows t, t+256, ... in order, then
-// a fixed tree over the 256 threads.  Rows are recomputed from the global statistics so that
+// Mean loss over the N rows by one workgroup: thread t sums rows t, t+1024, ... in order, then
+// a fixed tree over the 1024 threads.  Rows are recomputed from the global statistics so that
 // the per-row output stays optional.
-__global__ __launch_bounds__(256) void mean_loss_kernel(const float* __restrict__ gmax, const float* __restrict__ gsum,
-                                                        const float* __restrict__ ltgt, int p, int N, float* out) {
-    __shared__ float sh[4];
+__global__ __launch_bounds__(1024) void mean_loss_kernel(const float* __restrict__ gmax, const float* __restrict__ gsum,
+                                                         const float* __restrict__ ltgt, int p, int N, float* out) {
+    __shared__ float sh[16];
     float acc = 0.f;
-    for (int i = threadIdx.x; i < N; i += 256) {
+    for (int i = threadIdx.x; i < N; i += 1024) {
         float t = 0.f;
         for (int r = 0; r < p; ++r) t += ltgt[(size_t)r * N + i];
         acc += gmax[i] + logf(gsum[i]) - t;
     }
-    acc = block_sum256(acc, sh);
-    if (threadIdx.x == 0) out[0] = acc / (float)N;
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int w = 0; w < 16; ++w) s += sh[w];
+        out[0] = s / (float)N;
+    }
 }
 
 hipError_t launch_combine(const float* lmax, const float* lsum, const float* ltgt, int p, int N, float* gmax,
@@ -128,7 +134,7 @@ hipError_t launch_combine(const float* lmax, const float* lsum, const float* ltg
                        gmax, gsum, loss_row);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(256), 0, st, gmax, gsum, ltgt, p, N, loss_mean);
+    hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, st, gmax, gsum, ltgt, p, N, loss_mean);
     return hipGetLastError();
 }
 
@@ -148,7 +154,7 @@ __device__ __forceinline__ void st_from_f32(u16* p, float v) {
 }
 
 template <typename T, bool PRECISE>
-__global__ __launch_bounds__(256) void dlogits_kernel(const T* __restrict__ Y, T* __restrict__ D,
+__global__ __launch_bounds__(256) void dlogits_kernel(const T* Y, T* D,   // may alias (in place)
                                                       const int64_t* __restrict__ labels, int64_t off,
                                                       const float* __restrict__ gmax, const float* __restrict__ gsum,
                                                       float scale, int Vs) {
@@ -166,9 +172,72 @@ __global__ __launch_bounds__(256) void dlogits_kernel(const T* __restrict__ Y, T
     }
 }
 
+// Vector form: one thread per 16 bytes of a row (8 bf16 or 4 fp32); needs Vs % (16/sizeof(T)) == 0.
+template <typename T, bool PRECISE>
+__global__ __launch_bounds__(256) void dlogits_vec_kernel(const T* Y, T* D,   // may alias (in place)
+                                                          const int64_t* __restrict__ labels, int64_t off,
+                                                          const float* __restrict__ gmax, const float* __restrict__ gsum,
+                                                          float scale, int chunks_per_row, int64_t total_chunks) {
+    constexpr int E = 16 / (int)sizeof(T);
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= total_chunks) return;
+    const int i = (int)(c / chunks_per_row);
+    const int j0 = (int)(c - (int64_t)i * chunks_per_row) * E;
+    const float m = gmax[i];
+    const float inv = 1.0f / gsum[i];
+    const int64_t loc = labels[i] - off - j0;      // position of the label inside this chunk, if 0 <= loc < E
+    const uint4 raw = reinterpret_cast<const uint4*>(Y)[c];
+    const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+    float v[E];
+    if (sizeof(T) == 2) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[2 * e] = __uint_as_float(w[e] << 16);
+            v[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[e] = __uint_as_float(w[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const float x = v[e] - m;
+        float pr = (PRECISE ? expf(x) : __expf(x)) * inv;
+        if (loc == (int64_t)e) pr -= 1.0f;
+        v[e] = pr * scale;
+    }
+    uint4 o;
+    if (sizeof(T) == 2) {
+        unsigned q[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const __bf16 a = (__bf16)v[2 * e], b = (__bf16)v[2 * e + 1];
+            q[e] = (unsigned)__builtin_bit_cast(u16, a) | ((unsigned)__builtin_bit_cast(u16, b) << 16);
+        }
+        o = make_uint4(q[0], q[1], q[2], q[3]);
+    } else {
+        o = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[E > 2 ? 2 : 0]),
+                       __float_as_uint(v[E > 3 ? 3 : 0]));
+    }
+    reinterpret_cast<uint4*>(D)[c] = o;
+}
+
 hipError_t launch_dlogits(const void* Y, void* D, int is_bf16, const int64_t* labels, int64_t off, const float* gmax,
                           const float* gsum, float scale, int N, int Vs, hipStream_t st) {
     ProfScope prof(K_DLOGITS_EW, st);
+    const int E = is_bf16 ? 8 : 4;
+    if (Vs % E == 0 && ((((uintptr_t)Y) | ((uintptr_t)D)) & 15u) == 0) {
+        const int64_t total = (int64_t)N * (Vs / E);
+        const unsigned blocks = (unsigned)ceil_div(total, 256);
+        if (is_bf16) {
+            hipLaunchKernelGGL((dlogits_vec_kernel<u16, false>), dim3(blocks), dim3(256), 0, st, (const u16*)Y, (u16*)D,
+                               labels, off, gmax, gsum, scale, Vs / E, total);
+        } else {
+            hipLaunchKernelGGL((dlogits_vec_kernel<float, true>), dim3(blocks), dim3(256), 0, st, (const float*)Y,
+                               (float*)D, labels, off, gmax, gsum, scale, Vs / E, total);
+        }
+        return hipGetLastError();
+    }
     unsigned gx = (unsigned)ceil_div(Vs, 256);
     if (gx > 64) gx = 64;
     // grid.y carries the row; rows beyond 65535 are covered by launching in slabs
