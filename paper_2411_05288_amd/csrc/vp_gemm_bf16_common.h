@@ -2,8 +2,9 @@
 // the four epilogues (softmax statistics of pass S, the D matrix of pass T, fp32 store and
 // fp32 accumulate).
 //
-// Accumulator layout (both kernels): 256x256 output tile per workgroup of 4 wavefronts (2x2),
-// each wavefront owns 128x128 = 4x4 tiles of the 32x32x16 bf16 MFMA.  The MFMA is issued with
+// Accumulator layout (both kernels): 256x256 output tile per workgroup; the wavefronts form a
+// 2 x WN grid (WN = 2: four wavefronts of 128x128, WN = 4: eight wavefronts of 128x64), each
+// owning 4 x NJ tiles of the 32x32x16 bf16 MFMA (NJ = 128 / (32 WN) ... 4 or 2).  The MFMA is issued with
 // the B operand first, i.e. it produces the transposed 32x32 tile, so that register r of lane l
 // of tile (i, j) holds
 //        C[ i*32 + l%32 ][ j*32 + 8*(r/4) + 4*(l/32) + r%4 ]
@@ -82,20 +83,21 @@ __device__ __forceinline__ void store4_bf16(u16* row, int col, int n_cols, bool 
     }
 }
 
-// The LDS staging buffers are free when the epilogue runs; `smem` (>= 4 KB) carries the
-// exchange between the two wavefronts that share a row.
-template <Epi EPI>
-__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][4], const GemmBf16Params& g, int tile_m, int tile_n,
+// The LDS staging buffers are free when the epilogue runs; `smem` (>= 8 KB) carries the
+// exchange between the WN wavefronts that share a row.
+template <Epi EPI, int NJ, int WN>
+__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const GemmBf16Params& g, int tile_m, int tile_n,
                                               char* smem) {
+    constexpr int WCOLS = NJ * 32;            // columns owned by one wavefront
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, hf = lane >> 5;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     // element (i, j, r) of this lane: row = rbase + i*32, col = cbase + j*32 + 8*(r/4) + (r%4)
     const int rbase = m0 + wm * 128 + l32;
-    const int cbase = n0 + wn * 128 + 4 * hf;
+    const int cbase = n0 + wn * WCOLS + 4 * hf;
 
     if (EPI == Epi::StoreF32 || EPI == Epi::AccumF32) {
         const bool vec = (g.ldc % 4 == 0) && (((uintptr_t)g.C & 15u) == 0);
@@ -105,7 +107,7 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][4], const GemmB
             if (row < g.M) {
                 float* crow = g.C + (size_t)row * g.ldc;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < NJ; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         store4_f32<EPI == Epi::AccumF32>(crow, cbase + j * 32 + 8 * q, g.N, vec, acc[i][j][4 * q],
@@ -127,10 +129,10 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][4], const GemmB
                 const float inv = 1.0f / g.gsum[row];
                 const int64_t lab64 = g.labels[row] - g.shard_offset - cbase;
                 // column of the label relative to cbase, or -1 when it is not in this lane's range
-                const int lab = (lab64 >= 0 && lab64 < 128) ? (int)lab64 : -1;
+                const int lab = (lab64 >= 0 && lab64 < WCOLS) ? (int)lab64 : -1;
                 u16* drow = g.Y + (size_t)row * g.ldy;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < NJ; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         float d[4];
@@ -152,22 +154,22 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][4], const GemmB
         // softmax rescaling).  A lane reduces its 64 columns of a row in registers, one
         // exchange with lane ^ 32 completes the wavefront's 128 columns, and the two wavefronts
         // that share the row meet in LDS.
-        float* xm = reinterpret_cast<float*>(smem);          // [2][256]
-        float* xs = xm + 512;                                  // [2][256]
+        float* xm = reinterpret_cast<float*>(smem);          // [WN][256]
+        float* xs = xm + WN * 256;                             // [WN][256]
         const bool vec = g.Y && (g.ldy % 4 == 0) && (((uintptr_t)g.Y & 7u) == 0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = rbase + i * 32;
             float v = -INFINITY;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     if (cbase + j * 32 + 8 * (r >> 2) + (r & 3) < g.N) v = fmaxf(v, acc[i][j][r]);
             const float m = fmaxf(v, __shfl_xor(v, 32, 64));
             float s = 0.f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     if (cbase + j * 32 + 8 * (r >> 2) + (r & 3) < g.N) s += __expf(acc[i][j][r] - m);
@@ -179,11 +181,11 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][4], const GemmB
             }
             if (row < g.M) {
                 const int64_t lab64 = g.labels[row] - g.shard_offset - cbase;
-                if (lab64 >= 0 && lab64 < 128 && (lab64 & 4) == 0 && lab64 + cbase < g.N) {
+                if (lab64 >= 0 && lab64 < WCOLS && (lab64 & 4) == 0 && lab64 + cbase < g.N) {
                     const int lab = (int)lab64;
                     float t = 0.f;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < NJ; ++j)
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
                             if (lab == j * 32 + 8 * (r >> 2) + (r & 3)) t = acc[i][j][r];
@@ -192,7 +194,7 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][4], const GemmB
                 if (g.Y) {
                     u16* yrow = g.Y + (size_t)row * g.ldy;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < NJ; ++j)
 #pragma unroll
                         for (int q = 0; q < 4; ++q)
                             store4_bf16(yrow, cbase + j * 32 + 8 * q, g.N, vec, acc[i][j][4 * q], acc[i][j][4 * q + 1],
@@ -201,14 +203,18 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][4], const GemmB
             }
         }
         __syncthreads();
-        {
+        if (tid < 256) {
             const int row = m0 + tid;
             if (row < g.M) {
-                const float ma = xm[tid], mb = xm[256 + tid];
-                const float m = fmaxf(ma, mb);
+                float m = -INFINITY;
+#pragma unroll
+                for (int w = 0; w < WN; ++w) m = fmaxf(m, xm[w * 256 + tid]);
                 float s = 0.f;
-                if (ma > -INFINITY) s += xs[tid] * __expf(ma - m);
-                if (mb > -INFINITY) s += xs[256 + tid] * __expf(mb - m);
+#pragma unroll
+                for (int w = 0; w < WN; ++w) {
+                    const float mw = xm[w * 256 + tid];
+                    if (mw > -INFINITY) s += xs[w * 256 + tid] * __expf(mw - m);
+                }
                 g.part_max[(size_t)tile_n * g.M + row] = m;
                 g.part_sum[(size_t)tile_n * g.M + row] = s;
             }
