@@ -150,7 +150,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(GemmBf16Params g) {
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    mfma_tile(acc[i][j], af[i], bfr[j]);
+                    mfma_tile<EPI>(acc[i][j], af[i], bfr[j]);
         }
         if (more) {
             char* dA = smem + ((kt + 1) & 1) * STAGE_BYTES;

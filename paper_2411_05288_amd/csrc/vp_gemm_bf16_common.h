@@ -20,6 +20,7 @@ namespace vp {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = GEMM_BM, BN = GEMM_BN, BK = 64;
 constexpr int NT = 256;   // threads per workgroup
@@ -33,7 +34,12 @@ __device__ __forceinline__ u16 f32_to_bf16(float f) {
     return __builtin_bit_cast(u16, b);
 }
 
+constexpr float LOG2E = 1.44269504088896340736f;
+// 2^x with the hardware instruction (1 ulp, flushes results below 2^-126 to zero)
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // acc[i][j] += A-rows(i) x B-rows(j), stored transposed (see the layout above)
+template <Epi EPI>
 __device__ __forceinline__ void mfma_tile(floatx16& c, const bf16x8& a, const bf16x8& b) {
     c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c, 0, 0, 0);
 }
@@ -54,37 +60,91 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
     tn = in_panel / rows;
 }
 
-// Stores four consecutive values of a row at column `col` (a multiple of 4), clipped to n_cols.
-// vec: row start and leading dimension allow an aligned 16-byte (fp32) / 8-byte (bf16) access.
+// Stores four consecutive fp32 values of a row at column `col` (a multiple of 4), clipped to
+// n_cols.  vec: row start and leading dimension allow an aligned 16-byte access.
 template <bool ACCUM>
-__device__ __forceinline__ void store4_f32(float* row, int col, int n_cols, bool vec, float v0, float v1, float v2,
-                                           float v3) {
+__device__ __forceinline__ void store4_f32(float* row, int col, int n_cols, bool vec, const floatx4& v) {
     if (vec && col + 4 <= n_cols) {
         floatx4* p = reinterpret_cast<floatx4*>(row + col);
-        floatx4 v = {v0, v1, v2, v3};
-        if (ACCUM) v += *p;
-        *p = v;
+        *p = ACCUM ? v + *p : v;
     } else {
-        const float vals[4] = {v0, v1, v2, v3};
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if (col + e < n_cols) row[col + e] = ACCUM ? row[col + e] + vals[e] : vals[e];
+            if (col + e < n_cols) row[col + e] = ACCUM ? row[col + e] + v[e] : v[e];
     }
 }
-__device__ __forceinline__ void store4_bf16(u16* row, int col, int n_cols, bool vec, float v0, float v1, float v2,
-                                            float v3) {
-    if (vec && col + 4 <= n_cols) {
-        *reinterpret_cast<uint2*>(row + col) = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+// Stores eight consecutive bf16 values (bit patterns packed in a uint4) of a row at column `col`
+// (a multiple of 8), clipped to n_cols.
+__device__ __forceinline__ void store8_bf16(u16* row, int col, int n_cols, bool vec, const uint4& v) {
+    if (vec && col + 8 <= n_cols) {
+        *reinterpret_cast<uint4*>(row + col) = v;
     } else {
-        const float vals[4] = {v0, v1, v2, v3};
+        const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (col + e < n_cols) row[col + e] = f32_to_bf16(vals[e]);
+        for (int e = 0; e < 8; ++e)
+            if (col + e < n_cols) row[col + e] = (u16)(w[e >> 1] >> (16 * (e & 1)));
     }
 }
 
-// The LDS staging buffers are free when the epilogue runs; `smem` (>= 8 KB) carries the
-// exchange between the WN wavefronts that share a row.
+// Orders a wavefront's own LDS writes before its following LDS reads (and the reverse).  The
+// LDS executes one wavefront's accesses in program order; this only pins the program order.
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Output staging.  In the accumulator layout one store instruction would touch 32 different
+// rows with 32 (fp32) or 16 (bf16) bytes each, which the memory pipeline handles as 32 partial
+// cache-line writes.  Each wavefront therefore passes its results through a private LDS block
+// of 32 rows x WCOLS columns (rows padded by 16 bytes: conflict-free both ways) and stores
+// them row-contiguously: 16 bytes per lane, 512 (fp32) or 256 (bf16) contiguous bytes per row.
+constexpr int EPI_XCHG_BYTES = 8192;   // statistics exchange between wavefronts comes first
+
+template <int WCOLS>
+struct StageF32 {
+    static constexpr int RS = WCOLS * 4 + 16;     // row stride in bytes
+    static constexpr int BYTES = 32 * RS;
+    static constexpr int LPR = WCOLS / 4;         // lanes per row on the way out
+    static constexpr int RPI = 64 / LPR;          // rows per store instruction
+    static constexpr int STEPS = 32 / RPI;
+};
+template <int WCOLS>
+struct StageBf16 {
+    static constexpr int RS = WCOLS * 2 + 16;
+    static constexpr int BYTES = 32 * RS;
+    static constexpr int LPR = WCOLS / 8;
+    static constexpr int RPI = 64 / LPR;
+    static constexpr int STEPS = 32 / RPI;
+};
+
+// Wavefront-private staging block -> global memory, bf16: 16 bytes per lane, row-contiguous.
+template <typename St>
+__device__ __forceinline__ void flush_stage_bf16(const char* region, u16* Y, int ldy, int row_first, int M, int ocol,
+                                                 int N, bool vec, bool interior, int orow, int ochunk) {
+    if (interior) {
+        uintx4 v[St::STEPS];
+#pragma unroll
+        for (int s = 0; s < St::STEPS; ++s)
+            v[s] = *reinterpret_cast<const uintx4*>(region + (s * St::RPI + orow) * St::RS + ochunk * 16);
+#pragma unroll
+        for (int s = 0; s < St::STEPS; ++s) asm volatile("" : "+v"(v[s]));
+#pragma unroll
+        for (int s = 0; s < St::STEPS; ++s)
+            *reinterpret_cast<uintx4*>(Y + (size_t)(row_first + s * St::RPI + orow) * ldy + ocol) = v[s];
+    } else {
+#pragma unroll
+        for (int s = 0; s < St::STEPS; ++s) {
+            const int rr = s * St::RPI + orow;
+            const uint4 v = *reinterpret_cast<const uint4*>(region + rr * St::RS + ochunk * 16);
+            if (row_first + rr < M) store8_bf16(Y + (size_t)(row_first + rr) * ldy, ocol, N, vec, v);
+        }
+    }
+}
+
+// The LDS staging buffers of the main loop are free when the epilogue runs: `smem` (at least
+// EPI_XCHG_BYTES + wavefronts * StageF32<WCOLS>::BYTES, i.e. 74 KB) carries the statistics
+// exchange between the WN wavefronts that share a row, then one staging block per wavefront.
 template <Epi EPI, int NJ, int WN>
 __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const GemmBf16Params& g, int tile_m, int tile_n,
                                               char* smem) {
@@ -100,51 +160,110 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
     const int cbase = n0 + wn * WCOLS + 4 * hf;
 
     if (EPI == Epi::StoreF32 || EPI == Epi::AccumF32) {
+        typedef StageF32<WCOLS> St;
+        constexpr bool ACCUM = (EPI == Epi::AccumF32);
+        char* region = smem + EPI_XCHG_BYTES + wave * St::BYTES;
         const bool vec = (g.ldc % 4 == 0) && (((uintptr_t)g.C & 15u) == 0);
+        const int orow = lane / St::LPR, ochunk = lane % St::LPR;
+        const int col = n0 + wn * WCOLS + ochunk * 4;
+        const bool fullc = vec && (col + 4 <= g.N);
+        const bool interior = vec && (m0 + BM <= g.M) && (n0 + BN <= g.N);   // uniform over the workgroup
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int row = rbase + i * 32;
-            if (row < g.M) {
-                float* crow = g.C + (size_t)row * g.ldc;
+            const int row0 = m0 + wm * 128 + i * 32 + orow;
+            // the old values of C start their way from memory before the staging round trip
+            floatx4 cv[St::STEPS];
+            if (ACCUM) {
 #pragma unroll
-                for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        store4_f32<EPI == Epi::AccumF32>(crow, cbase + j * 32 + 8 * q, g.N, vec, acc[i][j][4 * q],
-                                                         acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
-                                                         acc[i][j][4 * q + 3]);
+                for (int s = 0; s < St::STEPS; ++s) {
+                    const int row = row0 + s * St::RPI;
+                    cv[s] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    if (fullc && row < g.M) cv[s] = *reinterpret_cast<const floatx4*>(g.C + (size_t)row * g.ldc + col);
+                }
             }
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const floatx4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    *reinterpret_cast<floatx4*>(region + l32 * St::RS + (j * 32 + 8 * q + 4 * hf) * 4) = v;
+                }
+            wave_lds_fence();
+            if (interior) {
+                // whole tile inside the matrix: all staged rows are fetched first, then stored
+                floatx4 v[St::STEPS];
+#pragma unroll
+                for (int s = 0; s < St::STEPS; ++s)
+                    v[s] = *reinterpret_cast<const floatx4*>(region + (s * St::RPI + orow) * St::RS + ochunk * 16);
+#pragma unroll
+                for (int s = 0; s < St::STEPS; ++s) asm volatile("" : "+v"(v[s]));
+#pragma unroll
+                for (int s = 0; s < St::STEPS; ++s) {
+                    if (ACCUM) v[s] += cv[s];
+                    *reinterpret_cast<floatx4*>(g.C + (size_t)(row0 + s * St::RPI) * g.ldc + col) = v[s];
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < St::STEPS; ++s) {
+                    const int rr = s * St::RPI + orow;
+                    const int row = row0 + s * St::RPI;
+                    floatx4 v = *reinterpret_cast<const floatx4*>(region + rr * St::RS + ochunk * 16);
+                    if (row < g.M) {
+                        float* crow = g.C + (size_t)row * g.ldc;
+                        if (fullc) {
+                            if (ACCUM) v += cv[s];
+                            *reinterpret_cast<floatx4*>(crow + col) = v;
+                        } else {
+                            store4_f32<ACCUM>(crow, col, g.N, false, v);
+                        }
+                    }
+                }
+            }
+            wave_lds_fence();
         }
     }
 
     if (EPI == Epi::DLogits) {
         // D = (softmax - G) * scale with the global statistics (pass T of Algorithm 1, with
         // the logits taken from the accumulators instead of memory)
-        const bool vec = (g.ldy % 4 == 0) && (((uintptr_t)g.Y & 7u) == 0);
+        typedef StageBf16<WCOLS> St;
+        char* region = smem + EPI_XCHG_BYTES + wave * St::BYTES;
+        const bool vec = (g.ldy % 8 == 0) && (((uintptr_t)g.Y & 15u) == 0);
+        const bool interior = vec && (m0 + BM <= g.M) && (n0 + BN <= g.N);   // uniform over the workgroup
+        const int orow = lane / St::LPR, ochunk = lane % St::LPR;
+        const int ocol = n0 + wn * WCOLS + ochunk * 8;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = rbase + i * 32;
-            if (row < g.M) {
-                const float m = g.gmax[row];
-                const float inv = 1.0f / g.gsum[row];
-                const int64_t lab64 = g.labels[row] - g.shard_offset - cbase;
-                // column of the label relative to cbase, or -1 when it is not in this lane's range
-                const int lab = (lab64 >= 0 && lab64 < WCOLS) ? (int)lab64 : -1;
-                u16* drow = g.Y + (size_t)row * g.ldy;
+            const int rowc = row < g.M ? row : g.M - 1;      // rows past the end compute on a copy, store nothing
+            const float m = g.gmax[rowc];
+            const float inv = 1.0f / g.gsum[rowc];
+            const int64_t lab64 = g.labels[rowc] - g.shard_offset - cbase;
+            // column of the label relative to cbase, or -1 when it is not in this lane's range
+            const int lab = (lab64 >= 0 && lab64 < WCOLS) ? (int)lab64 : -1;
+            const float ml2 = m * LOG2E;
+            const float f = inv * g.scale;
+            // the one-hot term touches at most one element per row: a wavefront-uniform branch
+            // keeps the 64 compares out of the common case
+            const bool any_label = __builtin_amdgcn_ballot_w64(lab >= 0) != 0;
 #pragma unroll
-                for (int j = 0; j < NJ; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float d[4];
+                for (int q = 0; q < 4; ++q) {
+                    float d[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            d[e] = __expf(acc[i][j][4 * q + e] - m) * inv;
-                            if (lab == j * 32 + 8 * q + e) d[e] -= 1.0f;
-                            d[e] *= g.scale;
-                        }
-                        store4_bf16(drow, cbase + j * 32 + 8 * q, g.N, vec, d[0], d[1], d[2], d[3]);
+                    for (int e = 0; e < 4; ++e) d[e] = exp2_fast(fmaf(acc[i][j][4 * q + e], LOG2E, -ml2)) * f;
+                    if (any_label) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (lab == j * 32 + 8 * q + e) d[e] -= g.scale;
                     }
-            }
+                    *reinterpret_cast<uint2*>(region + l32 * St::RS + (j * 32 + 8 * q + 4 * hf) * 2) =
+                        make_uint2(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]));
+                }
+            wave_lds_fence();
+            flush_stage_bf16<St>(region, g.Y, g.ldy, m0 + wm * 128 + i * 32, g.M, ocol, g.N, vec, interior, orow, ochunk);
+            wave_lds_fence();
         }
     }
 
@@ -154,52 +273,74 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
         // softmax rescaling).  A lane reduces its 64 columns of a row in registers, one
         // exchange with lane ^ 32 completes the wavefront's 128 columns, and the two wavefronts
         // that share the row meet in LDS.
+        typedef StageBf16<WCOLS> St;
+        char* region = smem + EPI_XCHG_BYTES + wave * St::BYTES;
         float* xm = reinterpret_cast<float*>(smem);          // [WN][256]
         float* xs = xm + WN * 256;                             // [WN][256]
-        const bool vec = g.Y && (g.ldy % 4 == 0) && (((uintptr_t)g.Y & 7u) == 0);
+        const bool vec = g.Y && (g.ldy % 8 == 0) && (((uintptr_t)g.Y & 15u) == 0);
+        const bool interior = vec && (m0 + BM <= g.M) && (n0 + BN <= g.N);   // uniform over the workgroup
+        const int orow = lane / St::LPR, ochunk = lane % St::LPR;
+        const int ocol = n0 + wn * WCOLS + ochunk * 8;
+        if (n0 + BN > g.N) {
+            // ragged last column tile: columns past the shard take -inf, which leaves the
+            // maximum alone and adds exp(-inf) = 0 to the sum
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (cbase + j * 32 + 8 * (r >> 2) + (r & 3) >= g.N) acc[i][j][r] = -INFINITY;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = rbase + i * 32;
-            float v = -INFINITY;
+            float v = acc[i][0][0];
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (cbase + j * 32 + 8 * (r >> 2) + (r & 3) < g.N) v = fmaxf(v, acc[i][j][r]);
+                for (int r = 0; r < 16; ++r) v = fmaxf(v, acc[i][j][r]);
             const float m = fmaxf(v, __shfl_xor(v, 32, 64));
+            // a wavefront whose 128 columns all lie past the shard has m = -inf; its sum is
+            // never used (the fold below skips it)
+            const float ml2 = m * LOG2E;
             float s = 0.f;
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (cbase + j * 32 + 8 * (r >> 2) + (r & 3) < g.N) s += __expf(acc[i][j][r] - m);
+                for (int r = 0; r < 16; ++r) s += exp2_fast(fmaf(acc[i][j][r], LOG2E, -ml2));
             s += __shfl_xor(s, 32, 64);
             if (hf == 0) {
                 const int lr = wm * 128 + i * 32 + l32;
                 xm[wn * 256 + lr] = m;
                 xs[wn * 256 + lr] = s;
             }
-            if (row < g.M) {
-                const int64_t lab64 = g.labels[row] - g.shard_offset - cbase;
-                if (lab64 >= 0 && lab64 < WCOLS && (lab64 & 4) == 0 && lab64 + cbase < g.N) {
-                    const int lab = (int)lab64;
+            {
+                const int64_t lab64 = (row < g.M ? g.labels[row] : (int64_t)-1) - g.shard_offset - cbase;
+                const bool mine = row < g.M && lab64 >= 0 && lab64 < WCOLS && (lab64 & 4) == 0 && lab64 + cbase < g.N;
+                // at most one element per row is a target logit: wavefront-uniform branch
+                if (__builtin_amdgcn_ballot_w64(mine) != 0) {
+                    const int lab = mine ? (int)lab64 : -1;
                     float t = 0.f;
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
                             if (lab == j * 32 + 8 * (r >> 2) + (r & 3)) t = acc[i][j][r];
-                    g.part_tgt[row] = t;
+                    if (mine) g.part_tgt[row] = t;
                 }
-                if (g.Y) {
-                    u16* yrow = g.Y + (size_t)row * g.ldy;
+            }
+            if (g.Y) {
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j)
+                for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            store4_bf16(yrow, cbase + j * 32 + 8 * q, g.N, vec, acc[i][j][4 * q], acc[i][j][4 * q + 1],
-                                        acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                }
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<uint2*>(region + l32 * St::RS + (j * 32 + 8 * q + 4 * hf) * 2) =
+                            make_uint2(pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]),
+                                       pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
+                wave_lds_fence();
+                flush_stage_bf16<St>(region, g.Y, g.ldy, m0 + wm * 128 + i * 32, g.M, ocol, g.N, vec, interior, orow, ochunk);
+                wave_lds_fence();
             }
         }
         __syncthreads();

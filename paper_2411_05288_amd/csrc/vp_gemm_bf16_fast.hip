@@ -138,12 +138,13 @@ __device__ __forceinline__ void read_frags(bf16x8 (&af)[4], bf16x8 (&bf)[4], con
     for (int t = 0; t < 4; ++t) bf[t] = read_operand<B_KC>(stage + TILE_BYTES, bbase, t, kk);
 }
 
+template <Epi EPI>
 __device__ __forceinline__ void mfma_step(floatx16 (&acc)[4][4], const bf16x8 (&af)[4], const bf16x8 (&bf)[4]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            mfma_tile(acc[i][j], af[i], bf[j]);
+            mfma_tile<EPI>(acc[i][j], af[i], bf[j]);
 }
 
 template <bool A_KC, bool B_KC, Epi EPI>
@@ -219,7 +220,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
         read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 1);                                           \
         issue_loads<6, 11>(g, a_bytes, b_bytes, (unsigned)((T) + 1) * a_kstep, (unsigned)((T) + 1) * b_kstep, \
                            avoff, bvoff, nxt, wave);                                                      \
-        mfma_step(acc, af0, bf0);                                                                        \
+        mfma_step<EPI>(acc, af0, bf0);                                                                        \
         _Pragma("unroll") for (int q = 0; q < 5; ++q) {                                                   \
             VP_SCHED_MFMA(3);                                                                            \
             VP_SCHED_DSRD((DS_PER_STEP + 4) / 5);                                                        \
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
         read_frags<A_KC, B_KC>(af0, bf0, cur, abase, bbase, 2);                                           \
         issue_loads<11, 16>(g, a_bytes, b_bytes, (unsigned)((T) + 1) * a_kstep,                           \
                             (unsigned)((T) + 1) * b_kstep, avoff, bvoff, nxt, wave);                      \
-        mfma_step(acc, af1, bf1);                                                                        \
+        mfma_step<EPI>(acc, af1, bf1);                                                                        \
         _Pragma("unroll") for (int q = 0; q < 5; ++q) {                                                   \
             VP_SCHED_MFMA(3);                                                                            \
             VP_SCHED_DSRD((DS_PER_STEP + 4) / 5);                                                        \
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
         }                                                                                                \
         VP_SCHED_MFMA(1);                                                                                \
         read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 3);                                           \
-        mfma_step(acc, af0, bf0);                                                                        \
+        mfma_step<EPI>(acc, af0, bf0);                                                                        \
         _Pragma("unroll") for (int q = 0; q < 4; ++q) {   /* operand reads early: they must have */     \
             VP_SCHED_MFMA(1);                               /* landed when the barrier is reached  */     \
             VP_SCHED_DSRD((DS_PER_STEP + 3) / 4);                                                        \
@@ -250,7 +251,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
         read_frags<A_KC, B_KC>(af0, bf0, nxt, abase, bbase, 0);                                           \
         issue_loads<0, 6>(g, a_bytes, b_bytes, (unsigned)((T) + 2) * a_kstep, (unsigned)((T) + 2) * b_kstep, \
                           avoff, bvoff, cur, wave);                                                       \
-        mfma_step(acc, af1, bf1);                                                                        \
+        mfma_step<EPI>(acc, af1, bf1);                                                                        \
         _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
             VP_SCHED_MFMA(3);                                                                            \
             VP_SCHED_DSRD((DS_PER_STEP + 5) / 6);                                                        \
