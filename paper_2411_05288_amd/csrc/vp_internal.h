@@ -18,7 +18,7 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 // Kernel ids for the optional per-kernel timing (names in vp_profile.hip, same order).
 enum KernelId : int {
     K_GEMM_FWD_STATS = 0, K_GEMM_DLOGITS, K_GEMM_DH, K_GEMM_DW, K_FOLD, K_COMBINE, K_DLOGITS_EW, K_GEMM_F32,
-    K_ROWSTATS_F32, K_EMBED_FWD, K_EMBED_KEYS, K_EMBED_SORT, K_EMBED_ACCUM, K_COUNT
+    K_ROWSTATS_F32, K_EMBED_FWD, K_EMBED_SORT, K_EMBED_ACCUM, K_COUNT
 };
 
 // Brackets the launches made during its lifetime with two events when timing is enabled;

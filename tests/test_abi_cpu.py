@@ -56,8 +56,8 @@ def test_workspace_sizes(lib):
     assert ws(2, 4096, 8192, 16000, 1, 0) == 4096 * 16000 * 2
     assert ws(2, 128, 256, 4096, 0, 1) == 128 * 4096 * 4
     assert ws(1, 128, 256, 4096, 0, 0) == 0 and ws(3, 128, 256, 4096, 1, 0) == 0
-    assert ws(4, 8192, 4096, 32000, 1, 0) == 8192 * 8
-    assert ws(4, 5000, 4096, 32000, 1, 0) == 8192 * 8          # padded to a power of two
+    assert ws(4, 8192, 4096, 32000, 1, 0) == 8192 * 12 + 256   # sorted keys, run starts, run counter
+    assert ws(4, 5000, 4096, 32000, 1, 0) == 8192 * 12 + 256   # padded to a power of two
     assert ws(0, 0, 256, 4096, 0, 0) == bad
     assert ws(0, 128, 256, 4096, 5, 0) == bad
     assert ws(0, 128, 256, 4096, 0, 2) == bad
