@@ -59,29 +59,60 @@ hipError_t launch_row_stats_f32(const float* Y, int64_t ldy, const int64_t* labe
     return hipGetLastError();
 }
 
-// Fold of the per-column-tile partial (max, sum-exp) pairs of one shard: the same online
-// rescaling as the cross-shard fold, in ascending tile order.
+// Fold of the per-column-tile partial (max, sum-exp) pairs of one shard with the same online
+// rescaling as the cross-shard fold.  A workgroup folds 64 token rows; wavefront g takes the
+// tiles congruent to g mod 4 (independent loads, several in flight), and the four partial
+// results meet in LDS in the fixed order g = 0..3.
 __global__ __launch_bounds__(256) void fold_partials_kernel(const float* __restrict__ pm, const float* __restrict__ ps,
                                                             const float* __restrict__ pt, int tiles, int N,
                                                             const int64_t* __restrict__ labels, int64_t off, int Vs,
                                                             float* lmax, float* lsum, float* ltgt) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= N) return;
-    float m = -INFINITY;
-    for (int t = 0; t < tiles; ++t) m = fmaxf(m, pm[(size_t)t * N + i]);
-    float s = 0.f;
-    for (int t = 0; t < tiles; ++t) s += ps[(size_t)t * N + i] * __expf(pm[(size_t)t * N + i] - m);
-    lmax[i] = m;
-    lsum[i] = s;
-    const int64_t loc = labels[i] - off;
-    ltgt[i] = (loc >= 0 && loc < Vs) ? pt[i] : 0.f;
+    __shared__ float xm[4][64], xs[4][64];
+    const int g = threadIdx.x >> 6, r = threadIdx.x & 63;
+    const int i = blockIdx.x * 64 + r;
+    const int ic = i < N ? i : N - 1;
+    float m = -INFINITY, s = 0.f;
+    int t = g;
+    for (; t + 12 < tiles; t += 16) {
+        float a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a[u] = pm[(size_t)(t + 4 * u) * N + ic];
+            b[u] = ps[(size_t)(t + 4 * u) * N + ic];
+        }
+        const float mn = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), m);
+        s *= __expf(m - mn);          // m = -inf only while s = 0: exp(-inf) = 0
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += b[u] * __expf(a[u] - mn);
+        m = mn;
+    }
+    for (; t < tiles; t += 4) {
+        const float a = pm[(size_t)t * N + ic], b = ps[(size_t)t * N + ic];
+        const float mn = fmaxf(a, m);
+        s = s * __expf(m - mn) + b * __expf(a - mn);
+        m = mn;
+    }
+    xm[g][r] = m;
+    xs[g][r] = s;
+    __syncthreads();
+    if (g == 0 && i < N) {
+        float mm = fmaxf(fmaxf(xm[0][r], xm[1][r]), fmaxf(xm[2][r], xm[3][r]));
+        float ss = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (xm[q][r] > -INFINITY) ss += xs[q][r] * __expf(xm[q][r] - mm);
+        lmax[i] = mm;
+        lsum[i] = ss;
+        const int64_t loc = labels[i] - off;
+        ltgt[i] = (loc >= 0 && loc < Vs) ? pt[i] : 0.f;
+    }
 }
 
 hipError_t launch_fold_partials(const float* pm, const float* ps, const float* pt, int tiles, int N,
                                 const int64_t* labels, int64_t off, int Vs, float* lmax, float* lsum, float* ltgt,
                                 hipStream_t st) {
     ProfScope prof(K_FOLD, st);
-    hipLaunchKernelGGL(fold_partials_kernel, dim3((unsigned)ceil_div(N, 256)), dim3(256), 0, st, pm, ps, pt, tiles, N,
+    hipLaunchKernelGGL(fold_partials_kernel, dim3((unsigned)ceil_div(N, 64)), dim3(256), 0, st, pm, ps, pt, tiles, N,
                        labels, off, Vs, lmax, lsum, ltgt);
     return hipGetLastError();
 }
