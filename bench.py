@@ -26,6 +26,13 @@ import numpy as np  # noqa: E402
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+# HBM-side traffic per launch of the GEMM kernels, from two rocprofv3 --pmc runs of this file
+# (FETCH_SIZE, WRITE_SIZE in KiB per dispatch; summary in profiles/output_layer_cfg2_llama.txt).
+# A plain 256 MiB copy in the same runs reads 0.5x its size on FETCH_SIZE and 1.0x on
+# WRITE_SIZE, hence the factors.  Counters cannot be read from inside this process.
+PMC_FETCH_FACTOR, PMC_WRITE_FACTOR = 2.0, 1.0
+PMC_KIB = {"cfg2_llama": {"gemm_bf16_fwd_stats": (103971.6, 47143.5), "gemm_bf16_dH": (132563.4, 65536.0),
+                          "gemm_bf16_dW": (99531.9, 64000.0)}}
 METRIC = "vocab-layer fwd+bwd TFLOP/s and tokens/s per GPU; % of bf16 MFMA peak"
 
 
@@ -111,9 +118,11 @@ def gemm_roofline(cfg, kernels):
     dom = max(names, key=lambda k: kernels[k]["ms_per_step"])
     flops_per_launch = 2.0 * cfg.N * cfg.h * cfg.Vs
     ach = flops_per_launch / (kernels[dom]["ms_per_launch"] * 1e-3) / 1e12
+    pmc = PMC_KIB.get(cfg.name, {}).get(dom)
+    traffic = None if pmc is None else (PMC_FETCH_FACTOR * pmc[0] + PMC_WRITE_FACTOR * pmc[1]) * 1024.0
     return {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": ach / BF16_MFMA_PEAK_TFLOPS, "flops_per_launch": flops_per_launch,
-            "avg_launch_ms": kernels[dom]["ms_per_launch"], "traffic": None}
+            "avg_launch_ms": kernels[dom]["ms_per_launch"], "traffic": traffic, "traffic_unit": "bytes per launch"}
 
 
 def cpu_baseline(cfg, sample_rows):
