@@ -198,47 +198,49 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
 #define VP_SCHED_VMEM(n) __builtin_amdgcn_sched_group_barrier(0x020, n, 0)
     constexpr int DS_PER_STEP = (A_KC ? 4 : 8) + (B_KC ? 4 : 8);   // LDS reads per 16-wide k sub-step
 
-    // prologue: tile 0 -> stage 0 completely, then the first part of tile 1 -> stage 1
+    // prologue: tile 0 -> stage 0 completely, then the first half of tile 1 -> stage 1
     issue_loads<0, 16>(g, a_bytes, b_bytes, 0u, 0u, avoff, bvoff, g_stage0, wave);
     __syncthreads();
-    issue_loads<0, 6>(g, a_bytes, b_bytes, a_kstep, b_kstep, avoff, bvoff, g_stage1, wave);
+    issue_loads<0, 8>(g, a_bytes, b_bytes, a_kstep, b_kstep, avoff, bvoff, g_stage1, wave);
     bf16x8 af0[4], bf0[4], af1[4], bf1[4];
     read_frags<A_KC, B_KC>(af0, bf0, g_stage0, abase, bbase, 0);
 
     // The k loop alternates two regions per 64-wide k tile T held in stage `cur`:
-    //  region 1: sub-steps 0..2 of tile T.  The loads 6..15 of tile T+1 (towards `nxt`) are spread
-    //            over the first two sub-steps, one every few MFMAs, so that no wavefront sits in
-    //            the (in-order) issue of a burst of global loads while its MFMA pipe runs dry.
-    //            It ends with the only barrier of the tile: tile T+1 has landed, and every
-    //            wavefront has fetched its last operands from `cur`.
+    //  region 1: sub-steps 0..2 of tile T.  The loads 8..15 of tile T+1 (towards `nxt`) are spread
+    //            over sub-step 0, one every two MFMAs, so that no wavefront sits in the (in-order)
+    //            issue of a burst of global loads while its MFMA pipe runs dry.  It ends with the
+    //            only barrier of the tile: tile T+1 has landed, and every wavefront has fetched
+    //            its last operands from `cur`.
     //  region 2: sub-step 3 of tile T, during which the first operands of tile T+1 are fetched
-    //            from `nxt` and the first six loads of tile T+2 start streaming into `cur`.
+    //            from `nxt` and the first eight loads of tile T+2 start streaming into `cur`.
+    // All sixteen loads of a tile are thus issued within the two sub-steps that follow the
+    // barrier freeing their stage, which leaves the last of them two sub-steps (about 1000
+    // cycles) to land before the next barrier; issuing part of them one sub-step later costs
+    // 4-8 % (measured), because the wavefronts then wait for memory at the barrier.
     // Loads past the end of K hit an empty descriptor and cost nothing.  The loop's back edge
     // sits right after a barrier, where no load is in flight.
+#define VP_MIX_LOADS()   /* 16 MFMAs, the sub-step's operand reads and 8 global loads */              \
+    _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                                       \
+        VP_SCHED_MFMA(2);                                                                                \
+        VP_SCHED_DSRD((DS_PER_STEP + 7) / 8);                                                            \
+        VP_SCHED_VMEM(1);                                                                                \
+    }
 #define VP_REGION1(cur, nxt, T)                                                                          \
     {                                                                                                    \
         read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 1);                                           \
-        issue_loads<6, 11>(g, a_bytes, b_bytes, (unsigned)((T) + 1) * a_kstep, (unsigned)((T) + 1) * b_kstep, \
+        issue_loads<8, 16>(g, a_bytes, b_bytes, (unsigned)((T) + 1) * a_kstep, (unsigned)((T) + 1) * b_kstep, \
                            avoff, bvoff, nxt, wave);                                                      \
-        mfma_step<EPI>(acc, af0, bf0);                                                                        \
-        _Pragma("unroll") for (int q = 0; q < 5; ++q) {                                                   \
-            VP_SCHED_MFMA(3);                                                                            \
-            VP_SCHED_DSRD((DS_PER_STEP + 4) / 5);                                                        \
-            VP_SCHED_VMEM(1);                                                                            \
-        }                                                                                                \
-        VP_SCHED_MFMA(1);                                                                                \
+        mfma_step<EPI>(acc, af0, bf0);                                                                   \
+        VP_MIX_LOADS()                                                                                   \
         read_frags<A_KC, B_KC>(af0, bf0, cur, abase, bbase, 2);                                           \
-        issue_loads<11, 16>(g, a_bytes, b_bytes, (unsigned)((T) + 1) * a_kstep,                           \
-                            (unsigned)((T) + 1) * b_kstep, avoff, bvoff, nxt, wave);                      \
-        mfma_step<EPI>(acc, af1, bf1);                                                                        \
+        mfma_step<EPI>(acc, af1, bf1);                                                                   \
         _Pragma("unroll") for (int q = 0; q < 5; ++q) {                                                   \
             VP_SCHED_MFMA(3);                                                                            \
             VP_SCHED_DSRD((DS_PER_STEP + 4) / 5);                                                        \
-            VP_SCHED_VMEM(1);                                                                            \
         }                                                                                                \
         VP_SCHED_MFMA(1);                                                                                \
         read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 3);                                           \
-        mfma_step<EPI>(acc, af0, bf0);                                                                        \
+        mfma_step<EPI>(acc, af0, bf0);                                                                   \
         _Pragma("unroll") for (int q = 0; q < 4; ++q) {   /* operand reads early: they must have */     \
             VP_SCHED_MFMA(1);                               /* landed when the barrier is reached  */     \
             VP_SCHED_DSRD((DS_PER_STEP + 3) / 4);                                                        \
@@ -249,19 +251,10 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
 #define VP_REGION2(cur, nxt, T)                                                                          \
     {                                                                                                    \
         read_frags<A_KC, B_KC>(af0, bf0, nxt, abase, bbase, 0);                                           \
-        issue_loads<0, 6>(g, a_bytes, b_bytes, (unsigned)((T) + 2) * a_kstep, (unsigned)((T) + 2) * b_kstep, \
+        issue_loads<0, 8>(g, a_bytes, b_bytes, (unsigned)((T) + 2) * a_kstep, (unsigned)((T) + 2) * b_kstep, \
                           avoff, bvoff, cur, wave);                                                       \
-        mfma_step<EPI>(acc, af1, bf1);                                                                        \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
-            VP_SCHED_MFMA(3);                                                                            \
-            VP_SCHED_DSRD((DS_PER_STEP + 5) / 6);                                                        \
-            VP_SCHED_VMEM(1);                                                                            \
-        }                                                                                                \
-        _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                                   \
-            VP_SCHED_MFMA(2);                                                                            \
-            VP_SCHED_DSRD((DS_PER_STEP + 5) / 6);                                                        \
-            VP_SCHED_VMEM(1);                                                                            \
-        }                                                                                                \
+        mfma_step<EPI>(acc, af1, bf1);                                                                   \
+        VP_MIX_LOADS()                                                                                   \
     }
 
     VP_REGION1(g_stage0, g_stage1, 0)
@@ -279,6 +272,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
         VP_REGION2(g_stage1, g_stage0, kt + 1)
     }
 #undef VP_REGION1
+#undef VP_MIX_LOADS
 #undef VP_REGION2
 #undef VP_SCHED_MFMA
 #undef VP_SCHED_DSRD
