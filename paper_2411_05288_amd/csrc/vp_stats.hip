@@ -188,14 +188,18 @@ template <typename T, bool PRECISE>
 __global__ __launch_bounds__(256) void dlogits_kernel(const T* Y, T* D,   // may alias (in place)
                                                       const int64_t* __restrict__ labels, int64_t off,
                                                       const float* __restrict__ gmax, const float* __restrict__ gsum,
-                                                      float scale, int Vs) {
+                                                      float scale, int Vs, int64_t ldd) {
     const int i = blockIdx.y;
     const float m = gmax[i];
     const float inv = 1.0f / gsum[i];
     const int64_t loc = labels[i] - off;
     const T* y = Y + (int64_t)i * Vs;
-    T* d = D + (int64_t)i * Vs;
-    for (int j = blockIdx.x * 256 + threadIdx.x; j < Vs; j += gridDim.x * 256) {
+    T* d = D + (int64_t)i * ldd;
+    for (int j = blockIdx.x * 256 + threadIdx.x; j < ldd; j += gridDim.x * 256) {
+        if (j >= Vs) {   // padding of the row: zero, because the dH product multiplies it by zero
+            st_from_f32(d + j, 0.f);
+            continue;
+        }
         const float v = ld_as_f32<T>(y + j) - m;
         float pr = (PRECISE ? expf(v) : __expf(v)) * inv;
         if ((int64_t)j == loc) pr -= 1.0f;
@@ -208,16 +212,21 @@ template <typename T, bool PRECISE>
 __global__ __launch_bounds__(256) void dlogits_vec_kernel(const T* Y, T* D,   // may alias (in place)
                                                           const int64_t* __restrict__ labels, int64_t off,
                                                           const float* __restrict__ gmax, const float* __restrict__ gsum,
-                                                          float scale, int chunks_per_row, int64_t total_chunks) {
+                                                          float scale, int chunks_per_row, int64_t total_chunks,
+                                                          int Vs, int64_t ldd) {
     constexpr int E = 16 / (int)sizeof(T);
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;   // chunk of D: chunks_per_row = ldd / E
     if (c >= total_chunks) return;
     const int i = (int)(c / chunks_per_row);
     const int j0 = (int)(c - (int64_t)i * chunks_per_row) * E;
+    if (j0 >= Vs) {   // padding of the row: zero, because the dH product multiplies it by zero
+        *reinterpret_cast<uint4*>(D + (int64_t)i * ldd + j0) = make_uint4(0u, 0u, 0u, 0u);
+        return;
+    }
     const float m = gmax[i];
     const float inv = 1.0f / gsum[i];
     const int64_t loc = labels[i] - off - j0;      // position of the label inside this chunk, if 0 <= loc < E
-    const uint4 raw = reinterpret_cast<const uint4*>(Y)[c];
+    const uint4 raw = *reinterpret_cast<const uint4*>(Y + (int64_t)i * Vs + j0);
     const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
     float v[E];
     if (sizeof(T) == 2) {
@@ -250,38 +259,55 @@ __global__ __launch_bounds__(256) void dlogits_vec_kernel(const T* Y, T* D,   //
         o = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[E > 2 ? 2 : 0]),
                        __float_as_uint(v[E > 3 ? 3 : 0]));
     }
-    reinterpret_cast<uint4*>(D)[c] = o;
+    *reinterpret_cast<uint4*>(D + (int64_t)i * ldd + j0) = o;
+}
+
+// Zeroes columns Vs .. ldd-1 of every row of the bf16 matrix D (recompute mode: the GEMM
+// epilogue that writes D stops at column Vs).
+__global__ __launch_bounds__(256) void zero_pad_columns_kernel(u16* D, int N, int Vs, int64_t ldd) {
+    const int pad = (int)(ldd - Vs);
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (int64_t)N * pad) return;
+    const int i = (int)(t / pad), j = (int)(t - (int64_t)i * pad);
+    D[(int64_t)i * ldd + Vs + j] = 0;
+}
+
+hipError_t launch_zero_pad_columns(void* D, int N, int Vs, int64_t ldd, hipStream_t st) {
+    if (ldd <= Vs) return hipSuccess;
+    hipLaunchKernelGGL(zero_pad_columns_kernel, dim3((unsigned)ceil_div((int64_t)N * (ldd - Vs), 256)), dim3(256), 0, st,
+                       (u16*)D, N, Vs, ldd);
+    return hipGetLastError();
 }
 
 hipError_t launch_dlogits(const void* Y, void* D, int is_bf16, const int64_t* labels, int64_t off, const float* gmax,
-                          const float* gsum, float scale, int N, int Vs, hipStream_t st) {
+                          const float* gsum, float scale, int N, int Vs, int64_t ldd, hipStream_t st) {
     ProfScope prof(K_DLOGITS_EW, st);
     const int E = is_bf16 ? 8 : 4;
-    if (Vs % E == 0 && ((((uintptr_t)Y) | ((uintptr_t)D)) & 15u) == 0) {
-        const int64_t total = (int64_t)N * (Vs / E);
+    if (Vs % E == 0 && ldd % E == 0 && ((((uintptr_t)Y) | ((uintptr_t)D)) & 15u) == 0) {
+        const int64_t total = (int64_t)N * (ldd / E);
         const unsigned blocks = (unsigned)ceil_div(total, 256);
         if (is_bf16) {
             hipLaunchKernelGGL((dlogits_vec_kernel<u16, false>), dim3(blocks), dim3(256), 0, st, (const u16*)Y, (u16*)D,
-                               labels, off, gmax, gsum, scale, Vs / E, total);
+                               labels, off, gmax, gsum, scale, (int)(ldd / E), total, Vs, ldd);
         } else {
             hipLaunchKernelGGL((dlogits_vec_kernel<float, true>), dim3(blocks), dim3(256), 0, st, (const float*)Y,
-                               (float*)D, labels, off, gmax, gsum, scale, Vs / E, total);
+                               (float*)D, labels, off, gmax, gsum, scale, (int)(ldd / E), total, Vs, ldd);
         }
         return hipGetLastError();
     }
-    unsigned gx = (unsigned)ceil_div(Vs, 256);
+    unsigned gx = (unsigned)ceil_div(ldd, 256);
     if (gx > 64) gx = 64;
     // grid.y carries the row; rows beyond 65535 are covered by launching in slabs
     for (int r0 = 0; r0 < N; r0 += 65535) {
         const int rows = (N - r0 < 65535) ? (N - r0) : 65535;
         if (is_bf16) {
             hipLaunchKernelGGL((dlogits_kernel<u16, false>), dim3(gx, rows), dim3(256), 0, st,
-                               (const u16*)Y + (int64_t)r0 * Vs, (u16*)D + (int64_t)r0 * Vs, labels + r0, off,
-                               gmax + r0, gsum + r0, scale, Vs);
+                               (const u16*)Y + (int64_t)r0 * Vs, (u16*)D + (int64_t)r0 * ldd, labels + r0, off,
+                               gmax + r0, gsum + r0, scale, Vs, ldd);
         } else {
             hipLaunchKernelGGL((dlogits_kernel<float, true>), dim3(gx, rows), dim3(256), 0, st,
-                               (const float*)Y + (int64_t)r0 * Vs, (float*)D + (int64_t)r0 * Vs, labels + r0, off,
-                               gmax + r0, gsum + r0, scale, Vs);
+                               (const float*)Y + (int64_t)r0 * Vs, (float*)D + (int64_t)r0 * ldd, labels + r0, off,
+                               gmax + r0, gsum + r0, scale, Vs, ldd);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

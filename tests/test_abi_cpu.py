@@ -54,6 +54,7 @@ def test_workspace_sizes(lib):
     assert ws(0, 128, 256, 4096, 0, 0) == 128 * 4096 * 4
     # bwd: D [N, Vs] in the storage type
     assert ws(2, 4096, 8192, 16000, 1, 0) == 4096 * 16000 * 2
+    assert ws(2, 4096, 4096, 4000, 1, 1) == 4096 * 4032 * 2        # rows of D padded to 128-byte multiples
     assert ws(2, 128, 256, 4096, 0, 1) == 128 * 4096 * 4
     assert ws(1, 128, 256, 4096, 0, 0) == 0 and ws(3, 128, 256, 4096, 1, 0) == 0
     assert ws(4, 8192, 4096, 32000, 1, 0) == 8192 * 12 + 256   # sorted keys, run starts, run counter
