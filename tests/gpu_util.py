@@ -29,6 +29,9 @@ def to_host_f64(t: torch.Tensor) -> np.ndarray:
 def run_output_layer(H, Ws, labels, save_logits=True, grad_scale=None):
     import paper_2411_05288_amd as vp
     plan = vp.driver.OutputLayerPlan(to_dev(H), [to_dev(w) for w in Ws], to_dev(labels), save_logits, grad_scale)
+    # workspace contents are undefined on entry: poison it (0xFFFF is a bf16 NaN, 0xFFFFFFFF an fp32 NaN) so
+    # that any read of scratch the library did not write first (e.g. the row padding of D) shows up
+    plan.workspace.fill_(0xFF)
     plan.step()
     torch.cuda.synchronize()
     return plan

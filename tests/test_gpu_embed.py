@@ -20,6 +20,7 @@ def run_embed(tables, ids, gout, dtable0=None):
     if dtable0 is not None:
         for d, d0 in zip(plan.dtable, dtable0):
             d.copy_(to_dev(d0))
+    plan.workspace.fill_(0xFF)       # scratch contents are undefined on entry
     plan.forward()
     plan.backward()
     torch.cuda.synchronize()
