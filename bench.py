@@ -27,12 +27,18 @@ import numpy as np  # noqa: E402
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 # HBM-side traffic per launch of the GEMM kernels, from two rocprofv3 --pmc runs of this file
-# (FETCH_SIZE, WRITE_SIZE in KiB per dispatch; summary in profiles/output_layer_cfg2_llama.txt).
+# (FETCH_SIZE, WRITE_SIZE in KiB per dispatch; summaries in profiles/output_layer_<config>.txt).
 # A plain 256 MiB copy in the same runs reads 0.5x its size on FETCH_SIZE and 1.0x on
 # WRITE_SIZE, hence the factors.  Counters cannot be read from inside this process.
 PMC_FETCH_FACTOR, PMC_WRITE_FACTOR = 2.0, 1.0
-PMC_KIB = {"cfg2_llama": {"gemm_bf16_fwd_stats": (103971.6, 47143.5), "gemm_bf16_dH": (132563.4, 65536.0),
-                          "gemm_bf16_dW": (99531.9, 64000.0)}}
+PMC_KIB = {
+    "cfg2_llama": {"gemm_bf16_fwd_stats": (103971.6, 47143.5), "gemm_bf16_dH": (132563.4, 65536.0),
+                   "gemm_bf16_dW": (99531.9, 64000.0)},
+    "cfg3_large_vocab": {"gemm_bf16_fwd_stats": (501472.7, 157339.0), "gemm_bf16_dH": (562528.5, 65536.0),
+                         "gemm_bf16_dW": (568876.5, 256512.0)},
+    "cfg4_very_large_vocab": {"gemm_bf16_fwd_stats": (1017388.4, 28887.3), "gemm_bf16_dlogits": (1009282.2, 135936.0),
+                              "gemm_bf16_dH": (837943.6, 131073.6), "gemm_bf16_dW": (1512627.4, 512000.0)},
+}
 METRIC = "vocab-layer fwd+bwd TFLOP/s and tokens/s per GPU; % of bf16 MFMA peak"
 
 
@@ -203,6 +209,15 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     cfg = si.CONFIGS[args.config]
+    if isinstance(cfg, si.EmbedConfig):
+        # profiling aid: only the input-layer configuration, reported in GB/s of algorithmic bytes
+        emb = bench_embedding(vp, cfg, args.steps, args.warmup)
+        print(json.dumps({"metric": "input-layer gather + scatter-add, algorithmic HBM GB/s", "value": emb["fwd_GBs"],
+                          "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "config": {"workload": "%s: V=%d p=%d Vs=%d h=%d N=%d" % (cfg.name, cfg.V, cfg.p, cfg.Vs,
+                                                                                  cfg.h, cfg.N)},
+                          "embedding": emb}))
+        return
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
