@@ -31,23 +31,40 @@ class OutputLayerResult:
 
 
 class OutputLayerPlan:
-    """Buffers and launch order for one (N, h, Vs, p) output-layer workload."""
+    """Buffers and launch order for one output-layer workload of p shards.
+
+    Shards may have different numbers of rows (a short last shard); shard r owns the global
+    vocabulary rows [offsets[r], offsets[r] + rows_r).  ``vocab_size`` states the true
+    vocabulary when the table was padded to split evenly (the paper pads V to a multiple of
+    2p): rows at or beyond it are padding.  Padding never reaches the kernels -- a shard is
+    passed as its valid prefix, which is the same as giving the padded logits -inf -- and
+    the padding rows of dW are zero."""
 
     def __init__(self, H: torch.Tensor, W_shards: List[torch.Tensor], labels: torch.Tensor,
-                 save_logits: bool = True, grad_scale: Optional[float] = None):
+                 save_logits: bool = True, grad_scale: Optional[float] = None, vocab_size: Optional[int] = None):
         self.H, self.W, self.labels = H, W_shards, labels
         self.N, self.h = H.shape
         self.p = len(W_shards)
-        self.Vs = W_shards[0].shape[0]
+        self.rows = [int(w.shape[0]) for w in W_shards]
+        self.Vs = self.rows[0]
         for w in W_shards:
-            if tuple(w.shape) != (self.Vs, self.h):
-                raise B.VPError("all shards must be [Vs, h]")
+            if w.dim() != 2 or w.shape[1] != self.h:
+                raise B.VPError("every shard must be [rows, h]")
+        self.offsets = [0]
+        for n in self.rows[:-1]:
+            self.offsets.append(self.offsets[-1] + n)
+        total = self.offsets[-1] + self.rows[-1]
+        self.vocab_size = total if vocab_size is None else int(vocab_size)
+        if not 0 < self.vocab_size <= total:
+            raise B.VPError("vocab_size must be in (0, total rows]")
+        # valid (non-padding) rows of every shard
+        self.valid = [max(0, min(n, self.vocab_size - off)) for n, off in zip(self.rows, self.offsets)]
         self.dt = B.VP_F32 if H.dtype == torch.float32 else B.VP_BF16
         self.save_logits = save_logits
         self.grad_scale = (1.0 / self.N) if grad_scale is None else float(grad_scale)
         dev = H.device
         f32 = dict(dtype=torch.float32, device=dev)
-        N, h, p, Vs = self.N, self.h, self.p, self.Vs
+        N, h, p = self.N, self.h, self.p
         self.local_max = torch.empty((p, N), **f32)
         self.local_sumexp = torch.empty((p, N), **f32)
         self.local_target = torch.empty((p, N), **f32)
@@ -56,16 +73,26 @@ class OutputLayerPlan:
         self.loss_rows = torch.empty((N,), **f32)
         self.loss = torch.empty((1,), **f32)
         self.dH = torch.empty((N, h), **f32)
-        self.dW = [torch.empty((Vs, h), **f32) for _ in range(p)]
-        self.logits = [torch.empty((N, Vs), dtype=H.dtype, device=dev) for _ in range(p)] if save_logits else None
+        self.dW = [torch.empty((n, h), **f32) for n in self.rows]
+        self.logits = ([torch.empty((N, max(v, 1)), dtype=H.dtype, device=dev) for v in self.valid]
+                       if save_logits else None)
         flags = B.VP_SAVE_LOGITS if save_logits else 0
-        nbytes = max(B.vp_workspace_bytes(B.VP_CALL_OUTPUT_FWD, N, h, Vs, self.dt, flags),
-                     B.vp_workspace_bytes(B.VP_CALL_OUTPUT_BWD, N, h, Vs, self.dt, flags), 256)
+        nbytes = 256
+        for v in self.valid:
+            if v > 0:
+                nbytes = max(nbytes, B.vp_workspace_bytes(B.VP_CALL_OUTPUT_FWD, N, h, v, self.dt, flags),
+                             B.vp_workspace_bytes(B.VP_CALL_OUTPUT_BWD, N, h, v, self.dt, flags))
         self.workspace = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
 
     def forward(self, stream=None) -> None:
         for r in range(self.p):
-            B.vp_output_fwd(self.H, self.W[r], self.labels, r * self.Vs,
+            v = self.valid[r]
+            if v == 0:     # all padding: the neutral element of the combine (exp(-inf) = 0)
+                self.local_max[r].fill_(float("-inf"))
+                self.local_sumexp[r].zero_()
+                self.local_target[r].zero_()
+                continue
+            B.vp_output_fwd(self.H, self.W[r][:v], self.labels, self.offsets[r],
                             self.local_max[r], self.local_sumexp[r], self.local_target[r],
                             self.logits[r] if self.logits is not None else None, self.workspace, stream)
         B.vp_combine_stats(self.local_max, self.local_sumexp, self.local_target,
@@ -74,9 +101,14 @@ class OutputLayerPlan:
     def backward(self, stream=None) -> None:
         self.dH.zero_()
         for r in range(self.p):
-            B.vp_output_bwd(self.H, self.W[r], self.labels, r * self.Vs, self.global_max, self.global_sumexp,
+            v = self.valid[r]
+            if v < self.rows[r]:
+                self.dW[r][v:].zero_()
+            if v == 0:
+                continue
+            B.vp_output_bwd(self.H, self.W[r][:v], self.labels, self.offsets[r], self.global_max, self.global_sumexp,
                             self.logits[r] if self.logits is not None else None, self.grad_scale,
-                            self.dH, self.dW[r], self.workspace, stream)
+                            self.dH, self.dW[r][:v], self.workspace, stream)
 
     def step(self, stream=None) -> None:
         self.forward(stream)
@@ -88,9 +120,9 @@ class OutputLayerPlan:
                                  self.dH, self.dW, self.logits)
 
 
-def output_layer_step(H, W_shards, labels, save_logits=True, grad_scale=None) -> OutputLayerResult:
+def output_layer_step(H, W_shards, labels, save_logits=True, grad_scale=None, vocab_size=None) -> OutputLayerResult:
     """One forward + backward of the sharded output layer; returns all outputs."""
-    plan = OutputLayerPlan(H, W_shards, labels, save_logits, grad_scale)
+    plan = OutputLayerPlan(H, W_shards, labels, save_logits, grad_scale, vocab_size)
     plan.step()
     return plan.result()
 

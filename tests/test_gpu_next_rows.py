@@ -1,0 +1,89 @@
+"""GPU parity of the variants beyond Algorithm 1 on equal shards: a short last shard and a
+padded vocabulary (the paper pads V to a multiple of 2p), and tied input / output embeddings
+(one fp32 gradient buffer per shard receives dW from vp_output_bwd and then the scatter-add of
+vp_embed_bwd).  Same bars as the main parity tests; the oracle is the unsharded definition on
+the true vocabulary."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import vp_oracle as oc
+from gpu_util import GRAD_TOL, LOSS_RTOL, rel_max_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def run_plan(H, Ws, labels, save_logits, vocab_size=None):
+    import paper_2411_05288_amd as vp
+    plan = vp.driver.OutputLayerPlan(to_dev(H), [to_dev(w) for w in Ws], to_dev(labels), save_logits,
+                                     vocab_size=vocab_size)
+    plan.workspace.fill_(0xFF)
+    plan.step()
+    torch.cuda.synchronize()
+    return plan
+
+
+def check_uneven(N, h, rows, V_true, dtype, save_logits, seed):
+    total = sum(rows)
+    W = si.normal((total, h), 0.08, dtype, seed, si.STREAM_W)
+    H = si.normal((N, h), 1.0, dtype, seed, si.STREAM_H)
+    labels = si.uniform_ids(N, V_true, seed)
+    Ws, off = [], 0
+    for n in rows:
+        Ws.append(np.ascontiguousarray(W[off:off + n]))
+        off += n
+    plan = run_plan(H, Ws, labels, save_logits, vocab_size=V_true)
+    ref = oc.output_layer(si.as_f64(H), si.as_f64(W[:V_true]), labels)
+    tol = GRAD_TOL[dtype]
+    loss = float(to_host(plan.loss)[0])
+    assert abs(loss - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+    assert rel_max_err(to_host(plan.dH).astype(np.float64), ref["dX"]) <= tol
+    dW = np.concatenate([to_host(w).astype(np.float64) for w in plan.dW])
+    assert rel_max_err(dW[:V_true], ref["dW"]) <= tol
+    assert (dW[V_true:] == 0).all(), "padding rows of dW must be zero"
+    stat_atol = 2e-3 if dtype == "bf16" else 2e-6 * max(1.0, float(np.abs(ref["Y"]).max()))
+    np.testing.assert_allclose(to_host(plan.global_max), ref["m"], rtol=0, atol=stat_atol)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("save_logits", [True, False])
+def test_short_last_shard(dtype, save_logits):
+    # three shards of 520, 520 and 300 rows: nothing is padding
+    check_uneven(200, 128, [520, 520, 300], 1340, dtype, save_logits, seed=41)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("save_logits", [True, False])
+def test_vocabulary_padded_to_a_multiple_of_2p(dtype, save_logits):
+    # V = 1003, p = 4: padded to 1008 = 4 x 252; the last shard holds 247 real rows and 5 of padding
+    check_uneven(150, 64, [252] * 4, 1003, dtype, save_logits, seed=42)
+
+
+def test_shard_that_is_all_padding():
+    # V = 300 on 4 shards of 128 rows: shard 2 has 44 real rows, shard 3 none
+    check_uneven(70, 64, [128] * 4, 300, "bf16", True, seed=43)
+
+
+def test_tied_embeddings_accumulate_into_one_gradient():
+    # the output layer's dW_shard and the input layer's table gradient share one fp32 buffer per shard
+    import paper_2411_05288_amd as vp
+    N, h, V, p = 260, 128, 1024, 2
+    Vs = V // p
+    H, Ws, labels = si.small_output_case(N, h, V, p, "bf16", seed=51, w_std=0.08)
+    ids = si.zipf_ids(N, V, 1.1, 52)
+    gout = si.normal((N, h), 1.0, "bf16", 53, si.STREAM_GRAD)
+    plan = run_plan(H, Ws, labels, True)              # dW_shard = D^T H (overwrites)
+    ws = torch.empty((vp.vp_workspace_bytes(vp.binding.VP_CALL_EMBED_BWD, N, h, Vs, vp.VP_BF16, 0),),
+                     dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    for r in range(p):                                 # then the embedding gradient adds into it
+        vp.vp_embed_bwd(to_dev(gout), to_dev(ids), r * Vs, plan.dW[r], ws)
+    torch.cuda.synchronize()
+    ref = oc.output_layer(si.as_f64(H), si.as_f64(np.concatenate(Ws)), labels)
+    for r in range(p):
+        dE = oc.embed_bwd(si.as_f64(gout), ids, r * Vs, Vs, np.zeros((Vs, h)))
+        want = ref["dW"][r * Vs:(r + 1) * Vs] + dE
+        got = to_host(plan.dW[r]).astype(np.float64)
+        # the embedding term is exact in fp32 up to summation rounding; the dW term carries the bf16 bar
+        assert np.abs(got - want).max() <= GRAD_TOL["bf16"] * np.abs(ref["dW"]).max() + 1e-5 * np.abs(dE).max()
