@@ -52,12 +52,15 @@ typedef enum {
     VP_CALL_COMBINE_STATS = 1,
     VP_CALL_OUTPUT_BWD = 2,
     VP_CALL_EMBED_FWD = 3,
-    VP_CALL_EMBED_BWD = 4
+    VP_CALL_EMBED_BWD = 4,
+    VP_CALL_OUTPUT_FWD_ALG2 = 5,
+    VP_CALL_OUTPUT_DX_ALG2 = 6
 } vp_call;
 
 /* flags */
 enum {
-    VP_SAVE_LOGITS = 1u /* fwd: store the logits; bwd: the stored logits are supplied */
+    VP_SAVE_LOGITS = 1u, /* fwd: store the logits; bwd: the stored logits are supplied */
+    VP_SKIP_DH = 2u      /* vp_output_bwd only: pass T of Algorithm 2, dW_shard alone (dH_accum may be NULL) */
 };
 
 /* Library version (major*10000 + minor*100 + patch). Host-only, no device work. */
@@ -117,6 +120,8 @@ vp_status vp_combine_stats(const float* local_max, const float* local_sumexp, co
  * grad_scale = 1/N gives the gradients of the mean loss, 1 the paper's unscaled form.
  * logits_saved != NULL (with VP_SAVE_LOGITS): Y is read from there ([N,Vs], type dt);
  * NULL: Y is recomputed from H and W_shard.
+ * With VP_SKIP_DH only dW_shard is formed (pass T of Algorithm 2, section 4.4, where the input
+ * gradient has already left through vp_output_dx_alg2); dH_accum is then ignored and may be NULL.
  */
 vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* labels,
                         int64_t N, int64_t h, int64_t Vs, int64_t shard_offset,
@@ -125,6 +130,39 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
                         const void* logits_saved, float grad_scale,
                         float* dH_accum, float* dW_shard,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Pass S of Algorithm 2 (section 4.4, one barrier instead of two) for one shard: everything
+ * vp_output_fwd produces, plus the two [N,h] matrices from which the input gradient is formed
+ * inside the barrier, before the global statistics are known:
+ *     A = softmax'(Y) W_shard,   softmax'_ij = exp(Y_ij - m'_i) / sum'_i      (fp32)
+ *     B = G W_shard              (row i = W_shard[labels[i] - shard_offset] when the shard owns
+ *                                 labels[i], else zero; type dt, an exact copy of rows of W)
+ *   A_out [N,h] : out, fp32.   B_out [N,h] : out, type dt.   Everything else as vp_output_fwd.
+ */
+vp_status vp_output_fwd_alg2(const void* H, const void* W_shard, const int64_t* labels,
+                             int64_t N, int64_t h, int64_t Vs, int64_t shard_offset,
+                             vp_dtype dt, uint32_t flags,
+                             float* local_max, float* local_sumexp, float* local_target,
+                             void* logits_out, float* A_out, void* B_out,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * This shard's term of the input gradient of Algorithm 2 (section 4.4, the identity
+ * dX = sum_r ( A_r * sum'_r e^{m'_r - m} / sum  -  B_r )), evaluated once the barrier has
+ * produced the global statistics:
+ *     dH_accum[i,:] += ( A[i,:] * c_i - B[i,:] ) * grad_scale,
+ *     c_i = local_sumexp[i] * exp(local_max[i] - global_max[i]) / global_sumexp[i]
+ * (c_i = 0 for a shard whose local_max is -inf).  Calling the p shards in ascending order is
+ * the deterministic reduce.  Pass T of Algorithm 2 is vp_output_bwd with VP_SKIP_DH.
+ *   A [N,h] : in, fp32.  B [N,h] : in, type dt.  local_* / global_* [N] : in, fp32.
+ *   dH_accum [N,h] : in/out, fp32.
+ */
+vp_status vp_output_dx_alg2(const float* A, const void* B,
+                            const float* local_max, const float* local_sumexp,
+                            const float* global_max, const float* global_sumexp,
+                            int64_t N, int64_t h, vp_dtype dt, float grad_scale,
+                            float* dH_accum, void* stream);
 
 /*
  * Input layer forward on one shard (appendix C): the full-size [N,h] output, row i being

@@ -16,12 +16,15 @@ import torch
 VP_F32 = 0
 VP_BF16 = 1
 VP_SAVE_LOGITS = 1
+VP_SKIP_DH = 2
 
 VP_CALL_OUTPUT_FWD = 0
 VP_CALL_COMBINE_STATS = 1
 VP_CALL_OUTPUT_BWD = 2
 VP_CALL_EMBED_FWD = 3
 VP_CALL_EMBED_BWD = 4
+VP_CALL_OUTPUT_FWD_ALG2 = 5
+VP_CALL_OUTPUT_DX_ALG2 = 6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -58,6 +61,10 @@ def load_library() -> ctypes.CDLL:
     lib.vp_combine_stats.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, vp, vp]
     lib.vp_output_bwd.restype = c.c_int
     lib.vp_output_bwd.argtypes = [vp, vp, vp, i64, i64, i64, i64, c.c_int, u32, vp, vp, vp, fl, vp, vp, vp, sz, vp]
+    lib.vp_output_fwd_alg2.restype = c.c_int
+    lib.vp_output_fwd_alg2.argtypes = [vp, vp, vp, i64, i64, i64, i64, c.c_int, u32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.vp_output_dx_alg2.restype = c.c_int
+    lib.vp_output_dx_alg2.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, c.c_int, fl, vp, vp]
     lib.vp_embed_fwd.restype = c.c_int
     lib.vp_embed_fwd.argtypes = [vp, vp, i64, i64, i64, i64, c.c_int, vp, vp]
     lib.vp_embed_bwd.restype = c.c_int
@@ -165,7 +172,8 @@ def vp_combine_stats(local_max, local_sumexp, local_target, global_max, global_s
 
 def vp_output_bwd(H, W_shard, labels, shard_offset: int, global_max, global_sumexp, logits_saved,
                   grad_scale: float, dH_accum, dW_shard, workspace, stream=None) -> None:
-    """Pass T for one shard: dH_accum += D W_shard, dW_shard = D^T H."""
+    """Pass T for one shard: dH_accum += D W_shard, dW_shard = D^T H.  dH_accum=None selects pass T of
+    Algorithm 2 (flag VP_SKIP_DH): only dW_shard is formed."""
     N, h = H.shape
     Vs = W_shard.shape[0]
     dt = _dtype_code(H)
@@ -176,12 +184,48 @@ def vp_output_bwd(H, W_shard, labels, shard_offset: int, global_max, global_sume
     wp, wb = _ws(workspace)
     st = load_library().vp_output_bwd(
         _ptr(H, "H"), _ptr(W_shard, "W_shard"), _ptr(labels, "labels", (torch.int64,), (N,)),
-        N, h, Vs, shard_offset, dt, VP_SAVE_LOGITS if logits_saved is not None else 0,
+        N, h, Vs, shard_offset, dt,
+        (VP_SAVE_LOGITS if logits_saved is not None else 0) | (VP_SKIP_DH if dH_accum is None else 0),
         _ptr(global_max, "global_max", f, (N,)), _ptr(global_sumexp, "global_sumexp", f, (N,)),
         _ptr(logits_saved, "logits_saved", same, (N, Vs)), float(grad_scale),
         _ptr(dH_accum, "dH_accum", f, (N, h)), _ptr(dW_shard, "dW_shard", f, (Vs, h)),
         wp, wb, _stream(stream))
     _check(st, "vp_output_bwd")
+
+
+def vp_output_fwd_alg2(H, W_shard, labels, shard_offset: int, local_max, local_sumexp, local_target,
+                       A_out, B_out, logits_out=None, workspace=None, stream=None) -> None:
+    """Pass S of Algorithm 2 for one shard: the outputs of vp_output_fwd plus A = softmax' W_shard
+    ([N, h] fp32) and B = G W_shard ([N, h], dtype of W)."""
+    N, h = H.shape
+    Vs = W_shard.shape[0]
+    dt = _dtype_code(H)
+    if _dtype_code(W_shard) != dt or W_shard.shape[1] != h:
+        raise VPError("W_shard must be [Vs, h] with the dtype of H")
+    same = (torch.float32,) if dt == VP_F32 else _BF16_LIKE
+    f = (torch.float32,)
+    wp, wb = _ws(workspace)
+    st = load_library().vp_output_fwd_alg2(
+        _ptr(H, "H"), _ptr(W_shard, "W_shard"), _ptr(labels, "labels", (torch.int64,), (N,)),
+        N, h, Vs, shard_offset, dt, VP_SAVE_LOGITS if logits_out is not None else 0,
+        _ptr(local_max, "local_max", f, (N,)), _ptr(local_sumexp, "local_sumexp", f, (N,)),
+        _ptr(local_target, "local_target", f, (N,)), _ptr(logits_out, "logits_out", same, (N, Vs)),
+        _ptr(A_out, "A_out", f, (N, h)), _ptr(B_out, "B_out", same, (N, h)), wp, wb, _stream(stream))
+    _check(st, "vp_output_fwd_alg2")
+
+
+def vp_output_dx_alg2(A, B, local_max, local_sumexp, global_max, global_sumexp, grad_scale: float, dH_accum,
+                      stream=None) -> None:
+    """dH_accum += (A * sum' e^{m'-m} / sum - B) * grad_scale: this shard's term of Algorithm 2's input gradient."""
+    N, h = A.shape
+    f = (torch.float32,)
+    dt = _dtype_code(B)
+    st = load_library().vp_output_dx_alg2(
+        _ptr(A, "A", f, (N, h)), _ptr(B, "B", None, (N, h)), _ptr(local_max, "local_max", f, (N,)),
+        _ptr(local_sumexp, "local_sumexp", f, (N,)), _ptr(global_max, "global_max", f, (N,)),
+        _ptr(global_sumexp, "global_sumexp", f, (N,)), N, h, dt, float(grad_scale),
+        _ptr(dH_accum, "dH_accum", f, (N, h)), _stream(stream))
+    _check(st, "vp_output_dx_alg2")
 
 
 def vp_embed_fwd(table_shard, ids, shard_offset: int, out, stream=None) -> None:

@@ -46,8 +46,20 @@ const char* vp_status_string(vp_status s) {
 }
 
 size_t vp_workspace_bytes(vp_call which, int64_t N, int64_t h, int64_t Vs, vp_dtype dt, uint32_t flags) {
-    if (!dtype_ok(dt) || (flags & ~(uint32_t)VP_SAVE_LOGITS)) return (size_t)-1;
+    const uint32_t allowed = which == VP_CALL_OUTPUT_BWD ? (uint32_t)(VP_SAVE_LOGITS | VP_SKIP_DH) : (uint32_t)VP_SAVE_LOGITS;
+    if (!dtype_ok(dt) || (flags & ~allowed)) return (size_t)-1;
     switch (which) {
+        case VP_CALL_OUTPUT_FWD_ALG2:
+            // the statistics partials of the forward pass, then the softmax' operand of A = softmax' W
+            if (!sizes_ok(N, h, Vs) || !sizes_supported(N, h, Vs)) return (size_t)-1;
+            if (dt == VP_BF16) {
+                if (N * d_row_stride(Vs) >= MAX_ELEMS) return (size_t)-1;
+                return align_up((size_t)(2 * fwd_tiles(Vs) + 1) * N * sizeof(float), 256) +
+                       align_up((size_t)N * d_row_stride(Vs) * 2, 256);
+            }
+            return align_up((size_t)N * Vs * sizeof(float), 256);
+        case VP_CALL_OUTPUT_DX_ALG2:
+            return 0;
         case VP_CALL_OUTPUT_FWD:
             if (!sizes_ok(N, h, Vs) || !sizes_supported(N, h, Vs)) return (size_t)-1;
             if (dt == VP_BF16) return align_up((size_t)(2 * fwd_tiles(Vs) + 1) * N * sizeof(float), 256);
@@ -127,14 +139,15 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
                         int64_t shard_offset, vp_dtype dt, uint32_t flags, const float* global_max,
                         const float* global_sumexp, const void* logits_saved, float grad_scale, float* dH_accum,
                         float* dW_shard, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!H || !W_shard || !labels || !global_max || !global_sumexp || !dH_accum || !dW_shard)
-        return VP_ERR_INVALID_ARG;
+    if (!H || !W_shard || !labels || !global_max || !global_sumexp || !dW_shard) return VP_ERR_INVALID_ARG;
+    if (!dH_accum && !(flags & VP_SKIP_DH)) return VP_ERR_INVALID_ARG;
     if (!sizes_ok(N, h, Vs) || !dtype_ok(dt) || shard_offset < 0) return VP_ERR_INVALID_ARG;
-    if (flags & ~(uint32_t)VP_SAVE_LOGITS) return VP_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)(VP_SAVE_LOGITS | VP_SKIP_DH)) return VP_ERR_INVALID_ARG;
     if (((flags & VP_SAVE_LOGITS) != 0) != (logits_saved != nullptr)) return VP_ERR_INVALID_ARG;
     if (!aligned16(H) || !aligned16(W_shard) || !aligned16(logits_saved) || !aligned16(workspace) ||
         !aligned16(dH_accum) || !aligned16(dW_shard))
         return VP_ERR_INVALID_ARG;
+    const bool skip_dh = (flags & VP_SKIP_DH) != 0;
     if (!sizes_supported(N, h, Vs)) return VP_ERR_UNSUPPORTED;
     const size_t need = vp_workspace_bytes(VP_CALL_OUTPUT_BWD, N, h, Vs, dt, flags);
     if (need == (size_t)-1) return VP_ERR_UNSUPPORTED;
@@ -147,8 +160,8 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
         const int64_t ldd = d_row_stride(Vs);
         const int vec_ok = (h % 8 == 0) ? 1 : 0;
         if (logits_saved) {
-            e = launch_dlogits(logits_saved, D, 1, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N,
-                               (int)Vs, ldd, st);
+            e = launch_dlogits(logits_saved, Vs, D, ldd, 1, labels, shard_offset, global_max, global_sumexp, grad_scale,
+                               (int)N, (int)Vs, st);
         } else {
             GemmBf16Params g{};
             g.A = (const u16*)H; g.B = (const u16*)W_shard;
@@ -164,7 +177,7 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
             if (e == hipSuccess) e = launch_zero_pad_columns(D, (int)N, (int)Vs, ldd, st);
         }
         if (e != hipSuccess) return VP_ERR_DEVICE;
-        {   // dH += D W_shard : M = N tokens, N = h, K = Vs; W_shard is stored [K][N]
+        if (!skip_dh) {   // dH += D W_shard : M = N tokens, N = h, K = Vs; W_shard is stored [K][N]
             GemmBf16Params g{};
             g.A = D; g.B = (const u16*)W_shard;
             g.M = (int)N; g.N = (int)h; g.K = (int)Vs;
@@ -199,12 +212,104 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
         if (e != hipSuccess) return VP_ERR_DEVICE;
         Y = D;   // D is formed in place
     }
-    e = launch_dlogits(Y, D, 0, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N, (int)Vs, Vs, st);
+    e = launch_dlogits(Y, Vs, D, Vs, 0, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N, (int)Vs, st);
     if (e != hipSuccess) return VP_ERR_DEVICE;
-    e = launch_gemm_f32(D, Vs, 1, (const float*)W_shard, 1, h, dH_accum, h, (int)N, (int)h, (int)Vs, true, st);
-    if (e != hipSuccess) return VP_ERR_DEVICE;
+    if (!skip_dh) {
+        e = launch_gemm_f32(D, Vs, 1, (const float*)W_shard, 1, h, dH_accum, h, (int)N, (int)h, (int)Vs, true, st);
+        if (e != hipSuccess) return VP_ERR_DEVICE;
+    }
     e = launch_gemm_f32(D, 1, Vs, (const float*)H, 1, h, dW_shard, h, (int)Vs, (int)h, (int)N, false, st);
     return dev(e);
+}
+
+vp_status vp_output_fwd_alg2(const void* H, const void* W_shard, const int64_t* labels, int64_t N, int64_t h,
+                             int64_t Vs, int64_t shard_offset, vp_dtype dt, uint32_t flags, float* local_max,
+                             float* local_sumexp, float* local_target, void* logits_out, float* A_out, void* B_out,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    if (!H || !W_shard || !labels || !local_max || !local_sumexp || !local_target || !A_out || !B_out)
+        return VP_ERR_INVALID_ARG;
+    if (!sizes_ok(N, h, Vs) || !dtype_ok(dt) || shard_offset < 0) return VP_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)VP_SAVE_LOGITS) return VP_ERR_INVALID_ARG;
+    if (((flags & VP_SAVE_LOGITS) != 0) != (logits_out != nullptr)) return VP_ERR_INVALID_ARG;
+    if (!aligned16(H) || !aligned16(W_shard) || !aligned16(logits_out) || !aligned16(workspace) ||
+        !aligned16(A_out) || !aligned16(B_out))
+        return VP_ERR_INVALID_ARG;
+    if (!sizes_supported(N, h, Vs)) return VP_ERR_UNSUPPORTED;
+    const size_t need = vp_workspace_bytes(VP_CALL_OUTPUT_FWD_ALG2, N, h, Vs, dt, flags);
+    if (need == (size_t)-1) return VP_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < need) return VP_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+
+    if (dt == VP_BF16) {
+        const int64_t tiles = fwd_tiles(Vs);
+        const int64_t ldd = d_row_stride(Vs);
+        float* pm = (float*)workspace;
+        float* ps = pm + tiles * N;
+        float* pt = ps + tiles * N;
+        u16* P = (u16*)((char*)workspace + align_up((size_t)(2 * tiles + 1) * N * sizeof(float), 256));
+        // the logits go to the caller's buffer when it keeps them, else into the softmax' buffer (in place)
+        u16* Y = logits_out ? (u16*)logits_out : P;
+        const int64_t ldy = logits_out ? Vs : ldd;
+        GemmBf16Params g{};
+        g.A = (const u16*)H; g.B = (const u16*)W_shard;
+        g.M = (int)N; g.N = (int)Vs; g.K = (int)h;
+        g.lda = (int)h; g.ldb = (int)h;
+        g.a_kcontig = 1; g.b_kcontig = 1;
+        g.vec_ok = (h % 8 == 0) ? 1 : 0;
+        g.epi = Epi::FwdStats;
+        g.Y = Y; g.ldy = (int)ldy;
+        g.labels = labels; g.shard_offset = shard_offset;
+        g.part_max = pm; g.part_sum = ps; g.part_tgt = pt;
+        if ((e = launch_gemm_bf16(g, st)) != hipSuccess) return VP_ERR_DEVICE;
+        if ((e = launch_fold_partials(pm, ps, pt, (int)tiles, (int)N, labels, shard_offset, (int)Vs, local_max,
+                                      local_sumexp, local_target, st)) != hipSuccess)
+            return VP_ERR_DEVICE;
+        // softmax' with the shard's own statistics (no one-hot term, scale 1), rows padded and zero-filled
+        if ((e = launch_dlogits(Y, ldy, P, ldd, 1, nullptr, shard_offset, local_max, local_sumexp, 1.0f, (int)N,
+                                (int)Vs, st)) != hipSuccess)
+            return VP_ERR_DEVICE;
+        GemmBf16Params a{};   // A = softmax' W_shard : M = N tokens, N = h, K = Vs; W_shard is stored [K][N]
+        a.A = P; a.B = (const u16*)W_shard;
+        a.M = (int)N; a.N = (int)h; a.K = (int)Vs;
+        a.lda = (int)ldd; a.ldb = (int)h;
+        a.a_kcontig = 1; a.b_kcontig = 0;
+        a.vec_ok = (h % 8 == 0) ? 1 : 0;
+        a.epi = Epi::StoreF32;
+        a.C = A_out; a.ldc = (int)h;
+        a.kernel_id = K_GEMM_A_ALG2;
+        if ((e = launch_gemm_bf16(a, st)) != hipSuccess) return VP_ERR_DEVICE;
+        return dev(launch_embed_fwd(W_shard, labels, (int)N, (int)h, (int)Vs, shard_offset, 2, B_out, st));
+    }
+
+    // fp32: logits in the caller's buffer or the workspace, softmax' in the workspace (in place when they coincide)
+    float* P = (float*)workspace;
+    float* Y = logits_out ? (float*)logits_out : P;
+    if ((e = launch_gemm_f32((const float*)H, h, 1, (const float*)W_shard, h, 1, Y, Vs, (int)N, (int)Vs, (int)h, false,
+                             st)) != hipSuccess)
+        return VP_ERR_DEVICE;
+    if ((e = launch_row_stats_f32(Y, Vs, labels, shard_offset, (int)N, (int)Vs, local_max, local_sumexp, local_target,
+                                  st)) != hipSuccess)
+        return VP_ERR_DEVICE;
+    if ((e = launch_dlogits(Y, Vs, P, Vs, 0, nullptr, shard_offset, local_max, local_sumexp, 1.0f, (int)N, (int)Vs,
+                            st)) != hipSuccess)
+        return VP_ERR_DEVICE;
+    if ((e = launch_gemm_f32(P, Vs, 1, (const float*)W_shard, 1, h, A_out, h, (int)N, (int)h, (int)Vs, false, st)) !=
+        hipSuccess)
+        return VP_ERR_DEVICE;
+    return dev(launch_embed_fwd(W_shard, labels, (int)N, (int)h, (int)Vs, shard_offset, 4, B_out, st));
+}
+
+vp_status vp_output_dx_alg2(const float* A, const void* B, const float* local_max, const float* local_sumexp,
+                            const float* global_max, const float* global_sumexp, int64_t N, int64_t h, vp_dtype dt,
+                            float grad_scale, float* dH_accum, void* stream) {
+    if (!A || !B || !local_max || !local_sumexp || !global_max || !global_sumexp || !dH_accum)
+        return VP_ERR_INVALID_ARG;
+    if (N < 1 || h < 1 || !dtype_ok(dt)) return VP_ERR_INVALID_ARG;
+    if (!aligned16(A) || !aligned16(B) || !aligned16(dH_accum)) return VP_ERR_INVALID_ARG;
+    if (N >= MAX_ELEMS || h >= MAX_ELEMS || N * h >= MAX_ELEMS) return VP_ERR_UNSUPPORTED;
+    return dev(launch_dx_alg2(A, B, dt == VP_BF16 ? 1 : 0, local_max, local_sumexp, global_max, global_sumexp, (int)N,
+                              (int)h, grad_scale, dH_accum, (hipStream_t)stream));
 }
 
 vp_status vp_embed_fwd(const void* table_shard, const int64_t* ids, int64_t N, int64_t h, int64_t Vs,

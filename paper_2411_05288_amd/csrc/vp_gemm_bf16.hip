@@ -172,7 +172,8 @@ static hipError_t launch_t(const GemmBf16Params& p, hipStream_t st) {
 
 hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st) {
     if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
-    const int kid = p.epi == Epi::FwdStats ? K_GEMM_FWD_STATS
+    const int kid = p.kernel_id ? p.kernel_id
+                  : p.epi == Epi::FwdStats ? K_GEMM_FWD_STATS
                   : p.epi == Epi::DLogits  ? K_GEMM_DLOGITS
                   : p.epi == Epi::AccumF32 ? K_GEMM_DH : K_GEMM_DW;
     ProfScope prof(kid, st);
@@ -182,6 +183,7 @@ hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st) {
     if (p.a_kcontig && p.b_kcontig && p.epi == Epi::FwdStats) return launch_t<true, true, Epi::FwdStats>(p, st);
     if (p.a_kcontig && p.b_kcontig && p.epi == Epi::DLogits) return launch_t<true, true, Epi::DLogits>(p, st);
     if (p.a_kcontig && !p.b_kcontig && p.epi == Epi::AccumF32) return launch_t<true, false, Epi::AccumF32>(p, st);
+    if (p.a_kcontig && !p.b_kcontig && p.epi == Epi::StoreF32) return launch_t<true, false, Epi::StoreF32>(p, st);
     if (!p.a_kcontig && !p.b_kcontig && p.epi == Epi::StoreF32) return launch_t<false, false, Epi::StoreF32>(p, st);
     return hipErrorInvalidValue;
 }

@@ -326,6 +326,7 @@ hipError_t launch_gemm_bf16_fast(const GemmBf16Params& p, hipStream_t st) {
     if (p.a_kcontig && p.b_kcontig && p.epi == Epi::FwdStats) return launch_fast_t<true, true, Epi::FwdStats>(p, st);
     if (p.a_kcontig && p.b_kcontig && p.epi == Epi::DLogits) return launch_fast_t<true, true, Epi::DLogits>(p, st);
     if (p.a_kcontig && !p.b_kcontig && p.epi == Epi::AccumF32) return launch_fast_t<true, false, Epi::AccumF32>(p, st);
+    if (p.a_kcontig && !p.b_kcontig && p.epi == Epi::StoreF32) return launch_fast_t<true, false, Epi::StoreF32>(p, st);
     if (!p.a_kcontig && !p.b_kcontig && p.epi == Epi::StoreF32) return launch_fast_t<false, false, Epi::StoreF32>(p, st);
     return hipErrorInvalidValue;
 }

@@ -18,7 +18,7 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 // Kernel ids for the optional per-kernel timing (names in vp_profile.hip, same order).
 enum KernelId : int {
     K_GEMM_FWD_STATS = 0, K_GEMM_DLOGITS, K_GEMM_DH, K_GEMM_DW, K_FOLD, K_COMBINE, K_DLOGITS_EW, K_GEMM_F32,
-    K_ROWSTATS_F32, K_EMBED_FWD, K_EMBED_SORT, K_EMBED_ACCUM, K_COUNT
+    K_ROWSTATS_F32, K_EMBED_FWD, K_EMBED_SORT, K_EMBED_ACCUM, K_GEMM_A_ALG2, K_DX_ALG2, K_COUNT
 };
 
 // Brackets the launches made during its lifetime with two events when timing is enabled;
@@ -70,6 +70,7 @@ struct GemmBf16Params {
     const float* gmax;   // DLogits: [M]
     const float* gsum;   // DLogits: [M]
     float scale;         // DLogits
+    int kernel_id;       // timing slot; 0 = chosen from the epilogue
 };
 
 // Dispatches to the fast kernel when its preconditions hold (and the environment variable
@@ -96,9 +97,15 @@ hipError_t launch_combine(const float* lmax, const float* lsum, const float* ltg
                           float* gmax, float* gsum, float* loss_row, float* loss_mean, hipStream_t st);
 
 // D = (exp(Y - m)/sum - onehot) * scale from stored logits; is_bf16 selects the type of Y and D.
-// Y is dense [N, Vs]; D has row stride ldd elements.
-hipError_t launch_dlogits(const void* Y, void* D, int is_bf16, const int64_t* labels, int64_t off,
-                          const float* gmax, const float* gsum, float scale, int N, int Vs, int64_t ldd,
+// Y has row stride ldy, D row stride ldd (elements); columns Vs..ldd-1 of D are zeroed.
+// labels == nullptr: no one-hot term (softmax' of Algorithm 2 with the local statistics).
+hipError_t launch_dlogits(const void* Y, int64_t ldy, void* D, int64_t ldd, int is_bf16, const int64_t* labels,
+                          int64_t off, const float* gmax, const float* gsum, float scale, int N, int Vs,
+                          hipStream_t st);
+
+// dH += (A * c - B) * scale with c_i = lsum_i exp(lmax_i - gmax_i) / gsum_i  (Algorithm 2)
+hipError_t launch_dx_alg2(const float* A, const void* B, int b_is_bf16, const float* lmax, const float* lsum,
+                          const float* gmax, const float* gsum, int N, int h, float scale, float* dH,
                           hipStream_t st);
 
 // Zeroes the padding columns Vs .. ldd-1 of the bf16 matrix D [N, ldd].

@@ -47,7 +47,7 @@ ProfScope::~ProfScope() {
 static const char* const kNames[K_COUNT] = {
     "gemm_bf16_fwd_stats", "gemm_bf16_dlogits", "gemm_bf16_dH", "gemm_bf16_dW", "fold_partials",
     "combine_stats", "dlogits_elementwise", "gemm_f32", "row_stats_f32", "embed_fwd",
-    "embed_bwd_sort", "embed_bwd_accum"};
+    "embed_bwd_sort", "embed_bwd_accum", "gemm_bf16_A_alg2", "dx_alg2"};
 
 }  // namespace vp
 

@@ -188,12 +188,12 @@ template <typename T, bool PRECISE>
 __global__ __launch_bounds__(256) void dlogits_kernel(const T* Y, T* D,   // may alias (in place)
                                                       const int64_t* __restrict__ labels, int64_t off,
                                                       const float* __restrict__ gmax, const float* __restrict__ gsum,
-                                                      float scale, int Vs, int64_t ldd) {
+                                                      float scale, int Vs, int64_t ldy, int64_t ldd) {
     const int i = blockIdx.y;
     const float m = gmax[i];
     const float inv = 1.0f / gsum[i];
-    const int64_t loc = labels[i] - off;
-    const T* y = Y + (int64_t)i * Vs;
+    const int64_t loc = labels ? labels[i] - off : (int64_t)-1;
+    const T* y = Y + (int64_t)i * ldy;
     T* d = D + (int64_t)i * ldd;
     for (int j = blockIdx.x * 256 + threadIdx.x; j < ldd; j += gridDim.x * 256) {
         if (j >= Vs) {   // padding of the row: zero, because the dH product multiplies it by zero
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(256) void dlogits_vec_kernel(const T* Y, T* D,   //
                                                           const int64_t* __restrict__ labels, int64_t off,
                                                           const float* __restrict__ gmax, const float* __restrict__ gsum,
                                                           float scale, int chunks_per_row, int64_t total_chunks,
-                                                          int Vs, int64_t ldd) {
+                                                          int Vs, int64_t ldy, int64_t ldd) {
     constexpr int E = 16 / (int)sizeof(T);
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;   // chunk of D: chunks_per_row = ldd / E
     if (c >= total_chunks) return;
@@ -225,8 +225,9 @@ __global__ __launch_bounds__(256) void dlogits_vec_kernel(const T* Y, T* D,   //
     }
     const float m = gmax[i];
     const float inv = 1.0f / gsum[i];
-    const int64_t loc = labels[i] - off - j0;      // position of the label inside this chunk, if 0 <= loc < E
-    const uint4 raw = *reinterpret_cast<const uint4*>(Y + (int64_t)i * Vs + j0);
+    // position of the label inside this chunk, if 0 <= loc < E
+    const int64_t loc = labels ? labels[i] - off - j0 : (int64_t)-1;
+    const uint4 raw = *reinterpret_cast<const uint4*>(Y + (int64_t)i * ldy + j0);
     const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
     float v[E];
     if (sizeof(T) == 2) {
@@ -279,19 +280,20 @@ hipError_t launch_zero_pad_columns(void* D, int N, int Vs, int64_t ldd, hipStrea
     return hipGetLastError();
 }
 
-hipError_t launch_dlogits(const void* Y, void* D, int is_bf16, const int64_t* labels, int64_t off, const float* gmax,
-                          const float* gsum, float scale, int N, int Vs, int64_t ldd, hipStream_t st) {
+hipError_t launch_dlogits(const void* Y, int64_t ldy, void* D, int64_t ldd, int is_bf16, const int64_t* labels,
+                          int64_t off, const float* gmax, const float* gsum, float scale, int N, int Vs,
+                          hipStream_t st) {
     ProfScope prof(K_DLOGITS_EW, st);
     const int E = is_bf16 ? 8 : 4;
-    if (Vs % E == 0 && ldd % E == 0 && ((((uintptr_t)Y) | ((uintptr_t)D)) & 15u) == 0) {
+    if (Vs % E == 0 && ldd % E == 0 && ldy % E == 0 && ((((uintptr_t)Y) | ((uintptr_t)D)) & 15u) == 0) {
         const int64_t total = (int64_t)N * (ldd / E);
         const unsigned blocks = (unsigned)ceil_div(total, 256);
         if (is_bf16) {
             hipLaunchKernelGGL((dlogits_vec_kernel<u16, false>), dim3(blocks), dim3(256), 0, st, (const u16*)Y, (u16*)D,
-                               labels, off, gmax, gsum, scale, (int)(ldd / E), total, Vs, ldd);
+                               labels, off, gmax, gsum, scale, (int)(ldd / E), total, Vs, ldy, ldd);
         } else {
             hipLaunchKernelGGL((dlogits_vec_kernel<float, true>), dim3(blocks), dim3(256), 0, st, (const float*)Y,
-                               (float*)D, labels, off, gmax, gsum, scale, (int)(ldd / E), total, Vs, ldd);
+                               (float*)D, labels, off, gmax, gsum, scale, (int)(ldd / E), total, Vs, ldy, ldd);
         }
         return hipGetLastError();
     }
@@ -300,19 +302,75 @@ hipError_t launch_dlogits(const void* Y, void* D, int is_bf16, const int64_t* la
     // grid.y carries the row; rows beyond 65535 are covered by launching in slabs
     for (int r0 = 0; r0 < N; r0 += 65535) {
         const int rows = (N - r0 < 65535) ? (N - r0) : 65535;
+        const int64_t* lab = labels ? labels + r0 : nullptr;
         if (is_bf16) {
             hipLaunchKernelGGL((dlogits_kernel<u16, false>), dim3(gx, rows), dim3(256), 0, st,
-                               (const u16*)Y + (int64_t)r0 * Vs, (u16*)D + (int64_t)r0 * ldd, labels + r0, off,
-                               gmax + r0, gsum + r0, scale, Vs, ldd);
+                               (const u16*)Y + (int64_t)r0 * ldy, (u16*)D + (int64_t)r0 * ldd, lab, off,
+                               gmax + r0, gsum + r0, scale, Vs, ldy, ldd);
         } else {
             hipLaunchKernelGGL((dlogits_kernel<float, true>), dim3(gx, rows), dim3(256), 0, st,
-                               (const float*)Y + (int64_t)r0 * Vs, (float*)D + (int64_t)r0 * ldd, labels + r0, off,
-                               gmax + r0, gsum + r0, scale, Vs, ldd);
+                               (const float*)Y + (int64_t)r0 * ldy, (float*)D + (int64_t)r0 * ldd, lab, off,
+                               gmax + r0, gsum + r0, scale, Vs, ldy, ldd);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// Input gradient of Algorithm 2 (section 4.4): dH += (A c - B) scale, one thread per 4 columns.
+template <typename TB>
+__global__ __launch_bounds__(256) void dx_alg2_kernel(const float* __restrict__ A, const TB* __restrict__ Bm,
+                                                      const float* __restrict__ lmax, const float* __restrict__ lsum,
+                                                      const float* __restrict__ gmax, const float* __restrict__ gsum,
+                                                      int h, int64_t total, float scale, float* dH, int vec) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (vec) {
+        const int q = h / 4;
+        if (t >= total) return;
+        const int i = (int)(t / q);
+        const int64_t e0 = (int64_t)i * h + (t - (int64_t)i * q) * 4;
+        const float ml = lmax[i];
+        const float c = (ml > -INFINITY) ? lsum[i] * expf(ml - gmax[i]) / gsum[i] : 0.f;
+        const float4 a = *reinterpret_cast<const float4*>(A + e0);
+        float b[4];
+        if (sizeof(TB) == 2) {
+            const uint2 w = *reinterpret_cast<const uint2*>(Bm + e0);
+            b[0] = __uint_as_float(w.x << 16); b[1] = __uint_as_float(w.x & 0xFFFF0000u);
+            b[2] = __uint_as_float(w.y << 16); b[3] = __uint_as_float(w.y & 0xFFFF0000u);
+        } else {
+            const float4 w = *reinterpret_cast<const float4*>(Bm + e0);
+            b[0] = w.x; b[1] = w.y; b[2] = w.z; b[3] = w.w;
+        }
+        float4 d = *reinterpret_cast<const float4*>(dH + e0);
+        d.x += (a.x * c - b[0]) * scale;
+        d.y += (a.y * c - b[1]) * scale;
+        d.z += (a.z * c - b[2]) * scale;
+        d.w += (a.w * c - b[3]) * scale;
+        *reinterpret_cast<float4*>(dH + e0) = d;
+    } else {
+        if (t >= total) return;
+        const int i = (int)(t / h);
+        const float ml = lmax[i];
+        const float c = (ml > -INFINITY) ? lsum[i] * expf(ml - gmax[i]) / gsum[i] : 0.f;
+        dH[t] += (A[t] * c - ld_as_f32<TB>(Bm + t)) * scale;
+    }
+}
+
+hipError_t launch_dx_alg2(const float* A, const void* B, int b_is_bf16, const float* lmax, const float* lsum,
+                          const float* gmax, const float* gsum, int N, int h, float scale, float* dH,
+                          hipStream_t st) {
+    ProfScope prof(K_DX_ALG2, st);
+    const int vec = (h % 4 == 0) ? 1 : 0;
+    const int64_t total = vec ? (int64_t)N * (h / 4) : (int64_t)N * h;
+    const unsigned blocks = (unsigned)ceil_div(total, 256);
+    if (b_is_bf16)
+        hipLaunchKernelGGL((dx_alg2_kernel<u16>), dim3(blocks), dim3(256), 0, st, A, (const u16*)B, lmax, lsum, gmax, gsum,
+                           h, total, scale, dH, vec);
+    else
+        hipLaunchKernelGGL((dx_alg2_kernel<float>), dim3(blocks), dim3(256), 0, st, A, (const float*)B, lmax, lsum, gmax,
+                           gsum, h, total, scale, dH, vec);
+    return hipGetLastError();
 }
 
 }  // namespace vp

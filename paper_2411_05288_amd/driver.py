@@ -3,7 +3,9 @@
 This is launch ordering and buffer ownership only.  It follows Algorithm 1 of the paper:
 pass S on every shard (vp_output_fwd), barrier C1 (vp_combine_stats, standing in for the two
 all-reduces), pass T on every shard (vp_output_bwd) with the reduce C2 realised as fp32
-accumulation into one dH buffer in ascending shard order.  All device buffers are allocated
+accumulation into one dH buffer in ascending shard order.  With algorithm=2 it follows
+Algorithm 2: pass S also forms A and B (vp_output_fwd_alg2), the input gradient is
+accumulated inside the single barrier (vp_output_dx_alg2), and pass T is dW alone.  All device buffers are allocated
 once, when the plan is built; a step allocates nothing.
 """
 from __future__ import annotations
@@ -41,7 +43,11 @@ class OutputLayerPlan:
     the padding rows of dW are zero."""
 
     def __init__(self, H: torch.Tensor, W_shards: List[torch.Tensor], labels: torch.Tensor,
-                 save_logits: bool = True, grad_scale: Optional[float] = None, vocab_size: Optional[int] = None):
+                 save_logits: bool = True, grad_scale: Optional[float] = None, vocab_size: Optional[int] = None,
+                 algorithm: int = 1):
+        if algorithm not in (1, 2):
+            raise B.VPError("algorithm must be 1 (two barriers) or 2 (one barrier)")
+        self.algorithm = algorithm
         self.H, self.W, self.labels = H, W_shards, labels
         self.N, self.h = H.shape
         self.p = len(W_shards)
@@ -77,11 +83,15 @@ class OutputLayerPlan:
         self.logits = ([torch.empty((N, max(v, 1)), dtype=H.dtype, device=dev) for v in self.valid]
                        if save_logits else None)
         flags = B.VP_SAVE_LOGITS if save_logits else 0
+        fwd_call = B.VP_CALL_OUTPUT_FWD if algorithm == 1 else B.VP_CALL_OUTPUT_FWD_ALG2
         nbytes = 256
         for v in self.valid:
             if v > 0:
-                nbytes = max(nbytes, B.vp_workspace_bytes(B.VP_CALL_OUTPUT_FWD, N, h, v, self.dt, flags),
+                nbytes = max(nbytes, B.vp_workspace_bytes(fwd_call, N, h, v, self.dt, flags),
                              B.vp_workspace_bytes(B.VP_CALL_OUTPUT_BWD, N, h, v, self.dt, flags))
+        # Algorithm 2 keeps A = softmax' W_r and B = G W_r of every shard until the barrier
+        self.A = [torch.empty((N, h), **f32) for _ in range(p)] if algorithm == 2 else None
+        self.Bm = [torch.empty((N, h), dtype=H.dtype, device=dev) for _ in range(p)] if algorithm == 2 else None
         self.workspace = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
 
     def forward(self, stream=None) -> None:
@@ -92,14 +102,28 @@ class OutputLayerPlan:
                 self.local_sumexp[r].zero_()
                 self.local_target[r].zero_()
                 continue
-            B.vp_output_fwd(self.H, self.W[r][:v], self.labels, self.offsets[r],
-                            self.local_max[r], self.local_sumexp[r], self.local_target[r],
-                            self.logits[r] if self.logits is not None else None, self.workspace, stream)
+            lg = self.logits[r] if self.logits is not None else None
+            if self.algorithm == 1:
+                B.vp_output_fwd(self.H, self.W[r][:v], self.labels, self.offsets[r],
+                                self.local_max[r], self.local_sumexp[r], self.local_target[r],
+                                lg, self.workspace, stream)
+            else:
+                B.vp_output_fwd_alg2(self.H, self.W[r][:v], self.labels, self.offsets[r],
+                                     self.local_max[r], self.local_sumexp[r], self.local_target[r],
+                                     self.A[r], self.Bm[r], lg, self.workspace, stream)
         B.vp_combine_stats(self.local_max, self.local_sumexp, self.local_target,
                            self.global_max, self.global_sumexp, self.loss_rows, self.loss, stream)
+        if self.algorithm == 2:
+            # still inside the one barrier of Algorithm 2: the input gradient leaves here
+            self.dH.zero_()
+            for r in range(self.p):
+                if self.valid[r] > 0:
+                    B.vp_output_dx_alg2(self.A[r], self.Bm[r], self.local_max[r], self.local_sumexp[r],
+                                        self.global_max, self.global_sumexp, self.grad_scale, self.dH, stream)
 
     def backward(self, stream=None) -> None:
-        self.dH.zero_()
+        if self.algorithm == 1:
+            self.dH.zero_()
         for r in range(self.p):
             v = self.valid[r]
             if v < self.rows[r]:
@@ -108,7 +132,7 @@ class OutputLayerPlan:
                 continue
             B.vp_output_bwd(self.H, self.W[r][:v], self.labels, self.offsets[r], self.global_max, self.global_sumexp,
                             self.logits[r] if self.logits is not None else None, self.grad_scale,
-                            self.dH, self.dW[r][:v], self.workspace, stream)
+                            self.dH if self.algorithm == 1 else None, self.dW[r][:v], self.workspace, stream)
 
     def step(self, stream=None) -> None:
         self.forward(stream)

@@ -61,7 +61,11 @@ def test_workspace_sizes(lib):
     assert ws(4, 5000, 4096, 32000, 1, 0) == 8192 * 12 + 256   # padded to a power of two
     assert ws(0, 0, 256, 4096, 0, 0) == bad
     assert ws(0, 128, 256, 4096, 5, 0) == bad
-    assert ws(0, 128, 256, 4096, 0, 2) == bad
+    assert ws(0, 128, 256, 4096, 0, 2) == bad                       # VP_SKIP_DH belongs to the backward call only
+    assert ws(2, 128, 256, 4096, 0, 2) == 128 * 4096 * 4
+    # Algorithm 2 forward: partials + the padded bf16 softmax' operand; fp32: one [N, Vs] matrix
+    assert ws(5, 4096, 4096, 4000, 1, 1) == (2 * 16 + 1) * 4096 * 4 + 4096 * 4032 * 2
+    assert ws(5, 128, 256, 4096, 0, 0) == 128 * 4096 * 4 and ws(6, 128, 256, 4096, 0, 0) == 0
     assert ws(9, 128, 256, 4096, 0, 0) == bad
     assert ws(2, 1 << 20, 256, 1 << 20, 1, 0) == bad               # N*Vs beyond 2^31 elements
 
@@ -91,6 +95,17 @@ def test_argument_validation_launches_nothing(lib):
     assert ebw(P, P, 8, 8, 8, 0, 1, P, None, 0, None) == VP_ERR_WORKSPACE
     assert ebw(P, P, 1 << 25, 8, 8, 0, 1, P, P, 1 << 40, None) == VP_ERR_UNSUPPORTED
     assert ebw(P, P, 8, 0, 8, 0, 1, P, P, 1 << 20, None) == VP_ERR_INVALID_ARG
+    # Algorithm 2: pass S with A and B, the input-gradient term, pass T without dH
+    fwd2, dx2 = lib.vp_output_fwd_alg2, lib.vp_output_dx_alg2
+    assert fwd2(P, P, P, 8, 8, 8, 0, 1, 0, P, P, P, None, None, P, P, 1 << 20, None) == VP_ERR_INVALID_ARG   # no A
+    assert fwd2(P, P, P, 8, 8, 8, 0, 1, 0, P, P, P, None, P, None, P, 1 << 20, None) == VP_ERR_INVALID_ARG   # no B
+    assert fwd2(P, P, P, 8, 8, 8, 0, 1, 2, P, P, P, None, P, P, P, 1 << 20, None) == VP_ERR_INVALID_ARG      # bad flag
+    assert fwd2(P, P, P, 8, 8, 8, 0, 1, 0, P, P, P, None, P, P, P, 64, None) == VP_ERR_WORKSPACE
+    assert dx2(P, P, P, P, P, P, 8, 8, 1, 1.0, None, None) == VP_ERR_INVALID_ARG
+    assert dx2(P, P, P, P, P, P, 0, 8, 1, 1.0, P, None) == VP_ERR_INVALID_ARG
+    assert dx2(P, P + 4, P, P, P, P, 8, 8, 1, 1.0, P, None) == VP_ERR_INVALID_ARG
+    assert bwd(P, P, P, 8, 8, 8, 0, 1, 2, P, P, None, 1.0, None, P, P, 8, None) == VP_ERR_WORKSPACE          # VP_SKIP_DH: dH may be NULL
+    assert bwd(P, P, P, 8, 8, 8, 0, 1, 4, P, P, None, 1.0, P, P, P, 1 << 20, None) == VP_ERR_INVALID_ARG
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -87,3 +87,62 @@ def test_tied_embeddings_accumulate_into_one_gradient():
         got = to_host(plan.dW[r]).astype(np.float64)
         # the embedding term is exact in fp32 up to summation rounding; the dW term carries the bf16 bar
         assert np.abs(got - want).max() <= GRAD_TOL["bf16"] * np.abs(ref["dW"]).max() + 1e-5 * np.abs(dE).max()
+
+
+# ------------------------------------------------------------------ Algorithm 2 (one barrier)
+def check_alg2(N, h, V, p, dtype, save_logits, seed, w_std=0.08):
+    import paper_2411_05288_amd as vp
+    H, Ws, labels = si.small_output_case(N, h, V, p, dtype, seed=seed, w_std=w_std)
+    plan = vp.driver.OutputLayerPlan(to_dev(H), [to_dev(w) for w in Ws], to_dev(labels), save_logits, algorithm=2)
+    plan.workspace.fill_(0xFF)
+    plan.forward()                       # pass S on every shard, the barrier, the input gradient
+    torch.cuda.synchronize()
+    X, W64 = si.as_f64(H), [si.as_f64(w) for w in Ws]
+    ref2 = oc.output_layer_alg2(X, W64, labels)
+    full = oc.output_layer(X, np.concatenate(W64), labels)
+    tol = GRAD_TOL[dtype]
+    # dH is complete after the forward phase: that is the point of Algorithm 2
+    assert rel_max_err(to_host(plan.dH).astype(np.float64), full["dX"]) <= tol
+    assert rel_max_err(to_host(plan.dH).astype(np.float64), ref2["dX"]) <= tol
+    for r in range(p):
+        A = to_host(plan.A[r]).astype(np.float64)
+        assert rel_max_err(A, ref2["A"][r]) <= tol, "A of shard %d" % r
+        Bm = to_host(plan.Bm[r])
+        want = si.as_f64(Ws[r])[np.clip(labels - r * (V // p), 0, V // p - 1)]
+        own = (labels >= r * (V // p)) & (labels < (r + 1) * (V // p))
+        want[~own] = 0.0
+        assert np.array_equal(si.as_f64(Bm), want), "B of shard %d is an exact gather" % r
+        assert np.array_equal(want, ref2["B"][r])
+    loss = float(to_host(plan.loss)[0])
+    assert abs(loss - full["loss"]) <= LOSS_RTOL * abs(full["loss"])
+    plan.backward()                      # pass T: dW only
+    torch.cuda.synchronize()
+    dW = np.concatenate([to_host(w).astype(np.float64) for w in plan.dW])
+    assert rel_max_err(dW, full["dW"]) <= tol
+    assert rel_max_err(dW, np.concatenate(ref2["dW"])) <= tol
+    return plan
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("save_logits", [True, False])
+@pytest.mark.parametrize("shape", [(300, 136, 1040, 2), (257, 64, 792, 3), (513, 72, 500, 2), (1, 8, 8, 2)])
+def test_algorithm2_matches_oracle(shape, save_logits, dtype):
+    N, h, V, p = shape
+    print("alg2 case", shape, save_logits, dtype, flush=True)
+    check_alg2(N, h, V, p, dtype, save_logits, seed=300 + N)
+
+
+def test_algorithm2_equals_algorithm1_on_the_gpu():
+    import paper_2411_05288_amd as vp
+    H, Ws, labels = si.small_output_case(520, 256, 2048, 4, "bf16", seed=61, w_std=0.08)
+    args = (to_dev(H), [to_dev(w) for w in Ws], to_dev(labels), True)
+    a = vp.driver.OutputLayerPlan(*args, algorithm=1)
+    b = vp.driver.OutputLayerPlan(*args, algorithm=2)
+    a.step()
+    b.step()
+    torch.cuda.synchronize()
+    assert torch.equal(a.loss, b.loss)
+    for x, y in zip(a.dW, b.dW):
+        assert torch.equal(x, y)         # pass T forms D and dW identically in both algorithms
+    # dH: D W (D rounded to bf16) against A c - B (softmax' rounded to bf16): same bar, not the same bits
+    assert rel_max_err(to_host(b.dH).astype(np.float64), to_host(a.dH).astype(np.float64)) <= 1e-2
