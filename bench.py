@@ -84,7 +84,7 @@ def profiled_steps(vp, step, steps):
             for k, (ms, n) in rec.items()}
 
 
-def make_output_plan(vp, cfg, seeded_numpy):
+def make_output_plan(vp, cfg, seeded_numpy, algorithm=1):
     """Inputs of an output-layer configuration in HBM.  seeded_numpy=True uses the host
     generator shared with the oracle tests; otherwise tensors of the same distribution are
     drawn on the GPU (only timed, never compared)."""
@@ -100,7 +100,7 @@ def make_output_plan(vp, cfg, seeded_numpy):
         tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
         H = (torch.randn((cfg.N, cfg.h), generator=g, device="cuda") * cfg.h_std).to(tdt)
         Ws = [(torch.randn((cfg.Vs, cfg.h), generator=g, device="cuda") * cfg.w_std).to(tdt) for _ in range(cfg.p)]
-    return vp.OutputLayerPlan(H, Ws, dev(labels), cfg.save_logits)
+    return vp.OutputLayerPlan(H, Ws, dev(labels), cfg.save_logits, algorithm=algorithm)
 
 
 def output_numbers(cfg, ms):
@@ -182,6 +182,48 @@ def bench_embedding(vp, cfg, steps, warmup):
     }
 
 
+def bench_barrier_overlap(vp, cfg, steps):
+    """The barrier's on-device work (vp_combine_stats) on a side stream of default priority while the
+    next pass S (a stand-in for the transformer work the paper overlaps its barriers with) runs on the
+    main stream.  Reports the three wall times per iteration; hidden = both ~ compute alone."""
+    import torch
+    pl = make_output_plan(vp, cfg, seeded_numpy=False)
+    pl.forward()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+
+    def compute():
+        vp.vp_output_fwd(pl.H, pl.W[0], pl.labels, 0, pl.local_max[0], pl.local_sumexp[0], pl.local_target[0],
+                         pl.logits[0] if pl.logits is not None else None, pl.workspace)
+
+    lm, ls, lt = pl.local_max.clone(), pl.local_sumexp.clone(), pl.local_target.clone()
+
+    def barrier(stream=None):
+        vp.vp_combine_stats(lm, ls, lt, pl.global_max, pl.global_sumexp, pl.loss_rows, pl.loss, stream)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def both():
+        side.wait_stream(main)
+        barrier(side)
+        compute()
+        main.wait_stream(side)
+
+    out = {"compute_ms": timed(compute), "barrier_ms": timed(barrier), "both_ms": timed(both)}
+    out["hidden_fraction_of_barrier"] = max(0.0, min(1.0, (out["compute_ms"] + out["barrier_ms"] - out["both_ms"])
+                                                   / out["barrier_ms"]))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -250,6 +292,16 @@ def main():
             per_config[name] = dict(output_numbers(c, w_ms), kernels=kern, roofline=gemm_roofline(c, kern))
             del pl
             torch.cuda.empty_cache()
+        # the same headline workload through Algorithm 2 (one barrier; same three products per shard)
+        pl = make_output_plan(vp, cfg, seeded_numpy=False, algorithm=2)
+        k_steps = max(3, min(args.steps, 10))
+        w_ms, _ = time_steps(pl.step, k_steps, 2)
+        kern = profiled_steps(vp, pl.step, k_steps)
+        per_config[cfg.name + "_algorithm2"] = dict(output_numbers(cfg, w_ms), kernels=kern)
+        del pl
+        torch.cuda.empty_cache()
+        per_config["barrier_overlap_" + cfg.name] = bench_barrier_overlap(vp, cfg, 50)
+        torch.cuda.empty_cache()
 
     out = {
         "metric": METRIC,
