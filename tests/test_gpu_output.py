@@ -144,3 +144,37 @@ def test_generic_gemm_kernel_on_aligned_shapes(monkeypatch):
     H, Ws, labels = si.small_output_case(300, 128, 1040, 2, "bf16", seed=3, w_std=0.08)
     check_against_oracle(H, Ws, labels, True, tag="generic kernel, stored logits")
     check_against_oracle(H, Ws, labels, False, tag="generic kernel, recompute")
+
+
+def test_step_can_be_captured_in_a_hip_graph():
+    # the library allocates nothing, synchronises nothing and records no memset: a whole step can be
+    # captured once and replayed.  Every replay is checked against the eager result, with eager work
+    # and synchronisations between the replays.
+    import paper_2411_05288_amd as vp
+    H, Ws, labels = si.small_output_case(300, 136, 1040, 2, "bf16", seed=17, w_std=0.08)
+    plan = vp.driver.OutputLayerPlan(to_dev(H), [to_dev(w) for w in Ws], to_dev(labels), True)
+    plan.step()
+    torch.cuda.synchronize()
+    want = [plan.loss.clone(), plan.dH.clone(), plan.dW[0].clone(), plan.dW[1].clone(), plan.local_sumexp.clone()]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        plan.step()
+    torch.cuda.synchronize()
+    for i in range(4):
+        plan.dH.fill_(3.0)
+        plan.loss.zero_()
+        plan.dW[1].fill_(-1.0)
+        plan.workspace.fill_(0xFF)
+        g.replay()
+        torch.cuda.synchronize()
+        got = [plan.loss, plan.dH, plan.dW[0], plan.dW[1], plan.local_sumexp]
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), "replay %d differs from the eager step" % i
+        plan.step()                      # eager work between replays
+        torch.cuda.synchronize()
