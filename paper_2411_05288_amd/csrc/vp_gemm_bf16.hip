@@ -160,7 +160,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(GemmBf16Params g) {
         __syncthreads();
     }
 
-    gemm_epilogue<EPI, 4, 2>(acc, g, tile_m, tile_n, smem, smem + EPI_XCHG_BYTES + wave * StageF32<128>::BYTES);
+    gemm_epilogue<EPI, 4, 2, false>(acc, g, tile_m, tile_n, smem, smem + EPI_XCHG_BYTES + wave * StageF32<128>::BYTES);
 }
 
 template <bool A_KC, bool B_KC, Epi EPI>

@@ -147,7 +147,7 @@ __device__ __forceinline__ void mfma_step(floatx16 (&acc)[4][4], const bf16x8 (&
             mfma_tile<EPI>(acc[i][j], af[i], bf[j]);
 }
 
-template <bool A_KC, bool B_KC, Epi EPI>
+template <bool A_KC, bool B_KC, Epi EPI, bool STREAM>
 __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -282,7 +282,8 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     // keep the epilogue's address arithmetic from being hoisted above the main loop, where it
     // would occupy registers (and spill) for the whole kernel
     asm volatile("" : "+s"(tile_m), "+s"(tile_n));
-    gemm_epilogue<EPI, 4, 2>(acc, g, tile_m, tile_n, g_stage0, g_stage0 + EPI_XCHG_BYTES + wave * StageF32<128>::BYTES);
+    gemm_epilogue<EPI, 4, 2, STREAM>(acc, g, tile_m, tile_n, g_stage0,
+                                     g_stage0 + EPI_XCHG_BYTES + wave * StageF32<128>::BYTES);
     __syncthreads();   // the epilogue's LDS exchange is over before the next tile streams in
     }   // persistent tile loop
 }
@@ -304,7 +305,11 @@ template <bool A_KC, bool B_KC, Epi EPI>
 static hipError_t launch_fast_t(const GemmBf16Params& p, hipStream_t st) {
     const int tiles = (int)(ceil_div(p.M, BM) * ceil_div(p.N, BN));
     const int cus = compute_unit_count();
-    hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI>), dim3(tiles < cus ? tiles : cus), dim3(NT), 0, st, p);
+    // more tiles than workgroups: outputs are streamed past the L2 (see gemm_epilogue)
+    if (tiles > cus)
+        hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI, true>), dim3(cus), dim3(NT), 0, st, p);
+    else
+        hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI, false>), dim3(tiles), dim3(NT), 0, st, p);
     return hipGetLastError();
 }
 
