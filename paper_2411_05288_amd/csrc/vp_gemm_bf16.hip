@@ -111,7 +111,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(GemmBf16Params g) {
 
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     int tile_m, tile_n;
-    tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tile_m, tile_n);
+    tile_of_block(blockIdx.x, gridDim.x, tiles_m * tiles_n, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     floatx16 acc[4][4];

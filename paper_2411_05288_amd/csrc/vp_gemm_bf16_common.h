@@ -44,20 +44,59 @@ __device__ __forceinline__ void mfma_tile(floatx16& c, const bf16x8& a, const bf
     c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c, 0, 0, 0);
 }
 
-// Workgroup id -> output tile.  Workgroups are handed to the 8 XCDs round-robin, so ids
-// congruent mod 8 share an L2: give each XCD one contiguous run of logical tiles, and walk
-// the tiles in panels of 8 tile-rows, so the 32 workgroups resident on an XCD cover a
-// compact patch and re-use each other's operand panels from that L2.
-__device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int tiles_n, int& tm, int& tn) {
-    const int x = b & 7, per = nb >> 3, rem = nb & 7;
-    const int logical = x * per + (x < rem ? x : rem) + (b >> 3);
-    constexpr int GM = 8;
-    const int panel = logical / (GM * tiles_n);
-    const int first_m = panel * GM;
-    const int rows = (tiles_m - first_m < GM) ? (tiles_m - first_m) : GM;
-    const int in_panel = logical - panel * GM * tiles_n;
-    tm = first_m + in_panel % rows;
-    tn = in_panel / rows;
+// Virtual workgroup id -> output tile.  v = round * nb + b with nb workgroups per round (one
+// tile each; the last round may be short), total = tiles_m * tiles_n.  Workgroups are handed to
+// the 8 XCDs round-robin, so ids congruent mod 8 share an L2; in both orders below the 32
+// workgroups of an XCD cover a patch of 8 x 4 tiles at a time and re-use each other's operand
+// panels from that L2 (12 panels for 32 tiles).
+//
+//  * Up to 16 tile rows (forward and dH products: the token dimension is short): every XCD gets
+//    one contiguous run of tiles, walked in panels of 8 tile rows, column by column.
+//  * More than 16 tile rows (dW products: the vocabulary dimension is long): tiles are ranked
+//    hierarchically - blocks of 16 x 16 tiles (row-block major), inside a block groups of 4
+//    columns, inside a group the upper and the lower 8 rows, column by column, all clipped at
+//    the edges of the grid so that the rank is a bijection - and in every round the 8 XCDs
+//    take the 8 sub-blocks of one block.  What misses the L2s is then shared in the
+//    memory-side cache: 32 distinct panels per 256 tiles instead of 68 (measured on dW: -5 %
+//    at 63 x 32 tiles, -1.5 % at 63 x 16; the other products lose 1-3 % with it).
+__device__ __forceinline__ void tile_of_block(int v, int nb, int total, int tiles_m, int tiles_n, int& tm, int& tn) {
+    if (tiles_m <= 16) {
+        // all rounds laid end to end: XCD x owns ranks [x * per + min(x, rem), ...)
+        const int round = v / nb, b = v - round * nb;
+        const int x = b & 7, per = total >> 3, rem = total & 7;
+        // (a workgroup count that is not a multiple of 8 with several rounds: plain order)
+        const int logical = ((nb & 7) != 0 && total > nb) ? v
+                                                          : x * per + (x < rem ? x : rem) + round * (nb >> 3) + (b >> 3);
+        constexpr int GM = 8;
+        const int panel = logical / (GM * tiles_n);
+        const int first_m = panel * GM;
+        const int rows = (tiles_m - first_m < GM) ? (tiles_m - first_m) : GM;
+        const int in_panel = logical - panel * GM * tiles_n;
+        tm = first_m + in_panel % rows;
+        tn = in_panel / rows;
+        return;
+    }
+    int logical = v;
+    {
+        const int round = v / nb, b = v - round * nb;
+        const int here = min(nb, total - round * nb);      // workgroups active in this round
+        if ((here & 7) == 0) logical = round * nb + (b & 7) * (here >> 3) + (b >> 3);
+    }
+    const int rb = logical / (16 * tiles_n);               // row-block of 16 tile rows
+    int rem = logical - rb * 16 * tiles_n;
+    const int hR = min(16, tiles_m - 16 * rb);
+    const int cb = rem / (hR * 16);                        // column-block of 16 tile columns
+    rem -= cb * hR * 16;
+    const int wC = min(16, tiles_n - 16 * cb);
+    const int sc = rem / (hR * 4);                         // group of 4 tile columns
+    rem -= sc * hR * 4;
+    const int w = min(4, wC - 4 * sc);
+    const int h0 = min(8, hR);
+    const int sr = rem >= h0 * w ? 1 : 0;                  // upper / lower 8 tile rows
+    rem -= sr * h0 * w;
+    const int hs = sr ? hR - h0 : h0;
+    tm = 16 * rb + 8 * sr + rem % hs;
+    tn = 16 * cb + 4 * sc + rem / hs;
 }
 
 // Stores four consecutive fp32 values of a row at column `col` (a multiple of 4), clipped to

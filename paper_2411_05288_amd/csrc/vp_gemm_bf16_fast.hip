@@ -173,7 +173,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     // order: v % 8 is the XCD of this workgroup for every tile it processes.
     for (int v = blockIdx.x; v < total_tiles; v += gridDim.x) {
     int tile_m, tile_n;
-    tile_of_block(v, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
+    tile_of_block(v, gridDim.x, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // accumulators are zeroed directly in the AGPR half of the register file: zeroing them as
