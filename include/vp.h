@@ -60,7 +60,9 @@ typedef enum {
 /* flags */
 enum {
     VP_SAVE_LOGITS = 1u, /* fwd: store the logits; bwd: the stored logits are supplied */
-    VP_SKIP_DH = 2u      /* vp_output_bwd only: pass T of Algorithm 2, dW_shard alone (dH_accum may be NULL) */
+    VP_SKIP_DH = 2u,     /* vp_output_bwd only: pass T of Algorithm 2, dW_shard alone (dH_accum may be NULL) */
+    VP_DH_OVERWRITE = 4u /* vp_output_bwd only: dH_accum = D W_shard instead of +=: the first term of the reduce C2,
+                            which saves zero-filling dH_accum and reading the zeros back */
 };
 
 /* Library version (major*10000 + minor*100 + patch). Host-only, no device work. */

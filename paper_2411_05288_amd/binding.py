@@ -17,6 +17,7 @@ VP_F32 = 0
 VP_BF16 = 1
 VP_SAVE_LOGITS = 1
 VP_SKIP_DH = 2
+VP_DH_OVERWRITE = 4
 
 VP_CALL_OUTPUT_FWD = 0
 VP_CALL_COMBINE_STATS = 1
@@ -171,9 +172,10 @@ def vp_combine_stats(local_max, local_sumexp, local_target, global_max, global_s
 
 
 def vp_output_bwd(H, W_shard, labels, shard_offset: int, global_max, global_sumexp, logits_saved,
-                  grad_scale: float, dH_accum, dW_shard, workspace, stream=None) -> None:
+                  grad_scale: float, dH_accum, dW_shard, workspace, stream=None, dh_overwrite: bool = False) -> None:
     """Pass T for one shard: dH_accum += D W_shard, dW_shard = D^T H.  dH_accum=None selects pass T of
-    Algorithm 2 (flag VP_SKIP_DH): only dW_shard is formed."""
+    Algorithm 2 (flag VP_SKIP_DH): only dW_shard is formed.  dh_overwrite=True (flag VP_DH_OVERWRITE)
+    writes dH_accum = D W_shard: the first term of the reduce, no zero-fill needed."""
     N, h = H.shape
     Vs = W_shard.shape[0]
     dt = _dtype_code(H)
@@ -185,7 +187,8 @@ def vp_output_bwd(H, W_shard, labels, shard_offset: int, global_max, global_sume
     st = load_library().vp_output_bwd(
         _ptr(H, "H"), _ptr(W_shard, "W_shard"), _ptr(labels, "labels", (torch.int64,), (N,)),
         N, h, Vs, shard_offset, dt,
-        (VP_SAVE_LOGITS if logits_saved is not None else 0) | (VP_SKIP_DH if dH_accum is None else 0),
+        (VP_SAVE_LOGITS if logits_saved is not None else 0) | (VP_SKIP_DH if dH_accum is None else 0)
+        | (VP_DH_OVERWRITE if (dh_overwrite and dH_accum is not None) else 0),
         _ptr(global_max, "global_max", f, (N,)), _ptr(global_sumexp, "global_sumexp", f, (N,)),
         _ptr(logits_saved, "logits_saved", same, (N, Vs)), float(grad_scale),
         _ptr(dH_accum, "dH_accum", f, (N, h)), _ptr(dW_shard, "dW_shard", f, (Vs, h)),

@@ -46,7 +46,8 @@ const char* vp_status_string(vp_status s) {
 }
 
 size_t vp_workspace_bytes(vp_call which, int64_t N, int64_t h, int64_t Vs, vp_dtype dt, uint32_t flags) {
-    const uint32_t allowed = which == VP_CALL_OUTPUT_BWD ? (uint32_t)(VP_SAVE_LOGITS | VP_SKIP_DH) : (uint32_t)VP_SAVE_LOGITS;
+    const uint32_t allowed =
+        which == VP_CALL_OUTPUT_BWD ? (uint32_t)(VP_SAVE_LOGITS | VP_SKIP_DH | VP_DH_OVERWRITE) : (uint32_t)VP_SAVE_LOGITS;
     if (!dtype_ok(dt) || (flags & ~allowed)) return (size_t)-1;
     switch (which) {
         case VP_CALL_OUTPUT_FWD_ALG2:
@@ -142,12 +143,14 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
     if (!H || !W_shard || !labels || !global_max || !global_sumexp || !dW_shard) return VP_ERR_INVALID_ARG;
     if (!dH_accum && !(flags & VP_SKIP_DH)) return VP_ERR_INVALID_ARG;
     if (!sizes_ok(N, h, Vs) || !dtype_ok(dt) || shard_offset < 0) return VP_ERR_INVALID_ARG;
-    if (flags & ~(uint32_t)(VP_SAVE_LOGITS | VP_SKIP_DH)) return VP_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)(VP_SAVE_LOGITS | VP_SKIP_DH | VP_DH_OVERWRITE)) return VP_ERR_INVALID_ARG;
+    if ((flags & VP_SKIP_DH) && (flags & VP_DH_OVERWRITE)) return VP_ERR_INVALID_ARG;
     if (((flags & VP_SAVE_LOGITS) != 0) != (logits_saved != nullptr)) return VP_ERR_INVALID_ARG;
     if (!aligned16(H) || !aligned16(W_shard) || !aligned16(logits_saved) || !aligned16(workspace) ||
         !aligned16(dH_accum) || !aligned16(dW_shard))
         return VP_ERR_INVALID_ARG;
     const bool skip_dh = (flags & VP_SKIP_DH) != 0;
+    const bool dh_overwrite = (flags & VP_DH_OVERWRITE) != 0;
     if (!sizes_supported(N, h, Vs)) return VP_ERR_UNSUPPORTED;
     const size_t need = vp_workspace_bytes(VP_CALL_OUTPUT_BWD, N, h, Vs, dt, flags);
     if (need == (size_t)-1) return VP_ERR_UNSUPPORTED;
@@ -184,7 +187,8 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
             g.lda = (int)ldd; g.ldb = (int)h;
             g.a_kcontig = 1; g.b_kcontig = 0;
             g.vec_ok = vec_ok;
-            g.epi = Epi::AccumF32;
+            g.epi = dh_overwrite ? Epi::StoreF32 : Epi::AccumF32;
+            g.kernel_id = K_GEMM_DH;
             g.C = dH_accum; g.ldc = (int)h;
             e = launch_gemm_bf16(g, st);
             if (e != hipSuccess) return VP_ERR_DEVICE;
@@ -215,7 +219,7 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
     e = launch_dlogits(Y, Vs, D, Vs, 0, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N, (int)Vs, st);
     if (e != hipSuccess) return VP_ERR_DEVICE;
     if (!skip_dh) {
-        e = launch_gemm_f32(D, Vs, 1, (const float*)W_shard, 1, h, dH_accum, h, (int)N, (int)h, (int)Vs, true, st);
+        e = launch_gemm_f32(D, Vs, 1, (const float*)W_shard, 1, h, dH_accum, h, (int)N, (int)h, (int)Vs, !dh_overwrite, st);
         if (e != hipSuccess) return VP_ERR_DEVICE;
     }
     e = launch_gemm_f32(D, 1, Vs, (const float*)H, 1, h, dW_shard, h, (int)Vs, (int)h, (int)N, false, st);

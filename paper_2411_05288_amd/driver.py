@@ -122,8 +122,7 @@ class OutputLayerPlan:
                                         self.global_max, self.global_sumexp, self.grad_scale, self.dH, stream)
 
     def backward(self, stream=None) -> None:
-        if self.algorithm == 1:
-            self.dH.zero_()
+        first = True      # the first shard that contributes overwrites dH (Algorithm 1): no zero-fill
         for r in range(self.p):
             v = self.valid[r]
             if v < self.rows[r]:
@@ -132,7 +131,9 @@ class OutputLayerPlan:
                 continue
             B.vp_output_bwd(self.H, self.W[r][:v], self.labels, self.offsets[r], self.global_max, self.global_sumexp,
                             self.logits[r] if self.logits is not None else None, self.grad_scale,
-                            self.dH if self.algorithm == 1 else None, self.dW[r][:v], self.workspace, stream)
+                            self.dH if self.algorithm == 1 else None, self.dW[r][:v], self.workspace, stream,
+                            dh_overwrite=first)
+            first = False
 
     def step(self, stream=None) -> None:
         self.forward(stream)
