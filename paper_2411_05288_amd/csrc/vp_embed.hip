@@ -11,6 +11,7 @@
 namespace vp {
 
 typedef unsigned long long u64;
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 constexpr u64 KEY_NONE = ~0ull;          // sorts after every real key
 constexpr int SORT_CHUNK = 16384;        // keys sorted inside one workgroup's LDS (128 KB)
 constexpr int SORT_THREADS = 1024;
@@ -23,13 +24,13 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const V* __restrict__ ta
     const int i = blockIdx.x;
     const int64_t loc = ids[i] - off;
     V* o = out + (size_t)i * row_vecs;
+    // the output is written once and read much later (by the reduce over shards): streaming stores
     if (loc >= 0 && loc < Vs) {
         const V* t = table + (size_t)loc * row_vecs;
-        for (int c = threadIdx.x; c < row_vecs; c += 256) o[c] = t[c];
+        for (int c = threadIdx.x; c < row_vecs; c += 256) __builtin_nontemporal_store(t[c], o + c);
     } else {
-        V z;
-        __builtin_memset(&z, 0, sizeof(V));
-        for (int c = threadIdx.x; c < row_vecs; c += 256) o[c] = z;
+        V z = V(0);
+        for (int c = threadIdx.x; c < row_vecs; c += 256) __builtin_nontemporal_store(z, o + c);
     }
 }
 
@@ -38,8 +39,8 @@ hipError_t launch_embed_fwd(const void* table, const int64_t* ids, int N, int h,
     const int64_t row_bytes = (int64_t)h * elem_bytes;
     ProfScope prof(K_EMBED_FWD, st);
     if (row_bytes % 16 == 0) {
-        hipLaunchKernelGGL((embed_fwd_kernel<uint4>), dim3(N), dim3(256), 0, st, (const uint4*)table, ids,
-                           (int)(row_bytes / 16), Vs, off, (uint4*)out);
+        hipLaunchKernelGGL((embed_fwd_kernel<uintx4>), dim3(N), dim3(256), 0, st, (const uintx4*)table, ids,
+                           (int)(row_bytes / 16), Vs, off, (uintx4*)out);
     } else if (elem_bytes == 4) {
         hipLaunchKernelGGL((embed_fwd_kernel<unsigned>), dim3(N), dim3(256), 0, st, (const unsigned*)table, ids, h, Vs,
                            off, (unsigned*)out);
