@@ -26,6 +26,16 @@ int64_t fwd_tiles(int64_t Vs) { return ceil_div(Vs, GEMM_BN); }
 // (worth 9 % on that product when Vs * 2 is not a multiple of 128).
 int64_t d_row_stride(int64_t Vs) { return (Vs + 63) / 64 * 64; }
 
+size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
+
+// fp32 path: bytes of K-slice scratch behind the [N, Vs] matrix at the start of the workspace
+size_t f32_fwd_scratch(int64_t N, int64_t h, int64_t Vs) { return gemm_f32_scratch_floats(N, Vs, h) * sizeof(float); }
+size_t f32_bwd_scratch(int64_t N, int64_t h, int64_t Vs) {
+    return max3(gemm_f32_scratch_floats(N, Vs, h), gemm_f32_scratch_floats(N, h, Vs), gemm_f32_scratch_floats(Vs, h, N)) *
+           sizeof(float);
+}
+size_t f32_matrix_bytes(int64_t N, int64_t Vs) { return align_up((size_t)N * Vs * sizeof(float), 256); }
+
 vp_status dev(hipError_t e) { return e == hipSuccess ? VP_OK : VP_ERR_DEVICE; }
 
 }  // namespace
@@ -58,21 +68,21 @@ size_t vp_workspace_bytes(vp_call which, int64_t N, int64_t h, int64_t Vs, vp_dt
                 return align_up((size_t)(2 * fwd_tiles(Vs) + 1) * N * sizeof(float), 256) +
                        align_up((size_t)N * d_row_stride(Vs) * 2, 256);
             }
-            return align_up((size_t)N * Vs * sizeof(float), 256);
+            return f32_matrix_bytes(N, Vs) + align_up(f32_bwd_scratch(N, h, Vs), 256);
         case VP_CALL_OUTPUT_DX_ALG2:
             return 0;
         case VP_CALL_OUTPUT_FWD:
             if (!sizes_ok(N, h, Vs) || !sizes_supported(N, h, Vs)) return (size_t)-1;
             if (dt == VP_BF16) return align_up((size_t)(2 * fwd_tiles(Vs) + 1) * N * sizeof(float), 256);
-            // fp32: the logits live in the workspace unless the caller keeps them
-            return (flags & VP_SAVE_LOGITS) ? 0 : align_up((size_t)N * Vs * sizeof(float), 256);
+            // fp32: the logits live in the workspace unless the caller keeps them; then K-slice scratch
+            return ((flags & VP_SAVE_LOGITS) ? 0 : f32_matrix_bytes(N, Vs)) + align_up(f32_fwd_scratch(N, h, Vs), 256);
         case VP_CALL_OUTPUT_BWD:
             if (!sizes_ok(N, h, Vs) || !sizes_supported(N, h, Vs)) return (size_t)-1;
             if (dt == VP_BF16) {
                 if (N * d_row_stride(Vs) >= MAX_ELEMS) return (size_t)-1;
                 return align_up((size_t)N * d_row_stride(Vs) * 2, 256);
             }
-            return align_up((size_t)N * Vs * 4, 256);
+            return f32_matrix_bytes(N, Vs) + align_up(f32_bwd_scratch(N, h, Vs), 256);
         case VP_CALL_EMBED_BWD:
             if (N < 1 || N > ((int64_t)1 << 24)) return (size_t)-1;
             return align_up(embed_bwd_workspace(N), 256);
@@ -118,8 +128,10 @@ vp_status vp_output_fwd(const void* H, const void* W_shard, const int64_t* label
                                         local_sumexp, local_target, st));
     }
     float* Y = logits_out ? (float*)logits_out : (float*)workspace;
+    float* scratch = f32_fwd_scratch(N, h, Vs) ? (float*)((char*)workspace + (logits_out ? 0 : f32_matrix_bytes(N, Vs)))
+                                               : nullptr;
     hipError_t e = launch_gemm_f32((const float*)H, h, 1, (const float*)W_shard, h, 1, Y, Vs, (int)N, (int)Vs, (int)h,
-                                   false, st);
+                                   false, scratch, st);
     if (e != hipSuccess) return VP_ERR_DEVICE;
     return dev(launch_row_stats_f32(Y, Vs, labels, shard_offset, (int)N, (int)Vs, local_max, local_sumexp,
                                     local_target, st));
@@ -209,20 +221,22 @@ vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* label
 
     // fp32: every step in fp32
     float* D = (float*)workspace;
+    float* scratch = f32_bwd_scratch(N, h, Vs) ? (float*)((char*)workspace + f32_matrix_bytes(N, Vs)) : nullptr;
     const float* Y = (const float*)logits_saved;
     if (!Y) {
         e = launch_gemm_f32((const float*)H, h, 1, (const float*)W_shard, h, 1, D, Vs, (int)N, (int)Vs, (int)h, false,
-                            st);
+                            scratch, st);
         if (e != hipSuccess) return VP_ERR_DEVICE;
         Y = D;   // D is formed in place
     }
     e = launch_dlogits(Y, Vs, D, Vs, 0, labels, shard_offset, global_max, global_sumexp, grad_scale, (int)N, (int)Vs, st);
     if (e != hipSuccess) return VP_ERR_DEVICE;
     if (!skip_dh) {
-        e = launch_gemm_f32(D, Vs, 1, (const float*)W_shard, 1, h, dH_accum, h, (int)N, (int)h, (int)Vs, !dh_overwrite, st);
+        e = launch_gemm_f32(D, Vs, 1, (const float*)W_shard, 1, h, dH_accum, h, (int)N, (int)h, (int)Vs, !dh_overwrite,
+                            scratch, st);
         if (e != hipSuccess) return VP_ERR_DEVICE;
     }
-    e = launch_gemm_f32(D, 1, Vs, (const float*)H, 1, h, dW_shard, h, (int)Vs, (int)h, (int)N, false, st);
+    e = launch_gemm_f32(D, 1, Vs, (const float*)H, 1, h, dW_shard, h, (int)Vs, (int)h, (int)N, false, scratch, st);
     return dev(e);
 }
 
@@ -289,8 +303,9 @@ vp_status vp_output_fwd_alg2(const void* H, const void* W_shard, const int64_t* 
     // fp32: logits in the caller's buffer or the workspace, softmax' in the workspace (in place when they coincide)
     float* P = (float*)workspace;
     float* Y = logits_out ? (float*)logits_out : P;
+    float* scratch = f32_bwd_scratch(N, h, Vs) ? (float*)((char*)workspace + f32_matrix_bytes(N, Vs)) : nullptr;
     if ((e = launch_gemm_f32((const float*)H, h, 1, (const float*)W_shard, h, 1, Y, Vs, (int)N, (int)Vs, (int)h, false,
-                             st)) != hipSuccess)
+                             scratch, st)) != hipSuccess)
         return VP_ERR_DEVICE;
     if ((e = launch_row_stats_f32(Y, Vs, labels, shard_offset, (int)N, (int)Vs, local_max, local_sumexp, local_target,
                                   st)) != hipSuccess)
@@ -298,7 +313,8 @@ vp_status vp_output_fwd_alg2(const void* H, const void* W_shard, const int64_t* 
     if ((e = launch_dlogits(Y, Vs, P, Vs, 0, nullptr, shard_offset, local_max, local_sumexp, 1.0f, (int)N, (int)Vs,
                             st)) != hipSuccess)
         return VP_ERR_DEVICE;
-    if ((e = launch_gemm_f32(P, Vs, 1, (const float*)W_shard, 1, h, A_out, h, (int)N, (int)h, (int)Vs, false, st)) !=
+    if ((e = launch_gemm_f32(P, Vs, 1, (const float*)W_shard, 1, h, A_out, h, (int)N, (int)h, (int)Vs, false, scratch,
+                             st)) !=
         hipSuccess)
         return VP_ERR_DEVICE;
     return dev(launch_embed_fwd(W_shard, labels, (int)N, (int)h, (int)Vs, shard_offset, 4, B_out, st));

@@ -79,10 +79,14 @@ hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st);
 bool gemm_bf16_fast_ok(const GemmBf16Params& p);
 hipError_t launch_gemm_bf16_fast(const GemmBf16Params& p, hipStream_t st);
 
-// Generic strided fp32 GEMM: C[m,n] (+)= sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk]
+// Generic strided fp32 GEMM: C[m,n] (+)= sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk].  scratch: nullptr or at
+// least gemm_f32_scratch_floats(M, N, K) floats (then small outputs with a long K are computed in K slices).
 hipError_t launch_gemm_f32(const float* A, int64_t sam, int64_t sak,
                            const float* B, int64_t sbn, int64_t sbk,
-                           float* C, int64_t ldc, int M, int N, int K, bool accumulate, hipStream_t st);
+                           float* C, int64_t ldc, int M, int N, int K, bool accumulate, float* scratch,
+                           hipStream_t st);
+// Floats of scratch with which launch_gemm_f32 cuts K into slices for this shape (0: it would not).
+size_t gemm_f32_scratch_floats(int64_t M, int64_t N, int64_t K);
 
 // Row statistics of stored fp32 logits (fp32 path): m', sum', t'
 hipError_t launch_row_stats_f32(const float* Y, int64_t ldy, const int64_t* labels, int64_t off,

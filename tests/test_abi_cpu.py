@@ -50,22 +50,24 @@ def test_workspace_sizes(lib):
     assert ws(0, 4096, 4096, 16032, 1, 1) == (2 * 63 + 1) * 4096 * 4
     assert ws(0, 4096, 4096, 16032, 1, 0) == (2 * 63 + 1) * 4096 * 4
     # fp32 fwd: logits live in the workspace only when they are not kept
-    assert ws(0, 128, 256, 4096, 0, 1) == 0
-    assert ws(0, 128, 256, 4096, 0, 0) == 128 * 4096 * 4
+    # (plus scratch for K slices when the output has few tiles: 2 slices of [128, 4096] here)
+    assert ws(0, 128, 256, 4096, 0, 1) == 2 * 128 * 4096 * 4
+    assert ws(0, 128, 256, 4096, 0, 0) == 128 * 4096 * 4 + 2 * 128 * 4096 * 4
+    assert ws(0, 4096, 4096, 4096, 0, 1) == 0                      # enough tiles: no slicing
     # bwd: D [N, Vs] in the storage type
     assert ws(2, 4096, 8192, 16000, 1, 0) == 4096 * 16000 * 2
     assert ws(2, 4096, 4096, 4000, 1, 1) == 4096 * 4032 * 2        # rows of D padded to 128-byte multiples
-    assert ws(2, 128, 256, 4096, 0, 1) == 128 * 4096 * 4
+    assert ws(2, 128, 256, 4096, 0, 1) == 128 * 4096 * 4 + 32 * 128 * 256 * 4   # fp32: D, then 32 K slices of dH
     assert ws(1, 128, 256, 4096, 0, 0) == 0 and ws(3, 128, 256, 4096, 1, 0) == 0
     assert ws(4, 8192, 4096, 32000, 1, 0) == 8192 * 12 + 256   # sorted keys, run starts, run counter
     assert ws(4, 5000, 4096, 32000, 1, 0) == 8192 * 12 + 256   # padded to a power of two
     assert ws(0, 0, 256, 4096, 0, 0) == bad
     assert ws(0, 128, 256, 4096, 5, 0) == bad
     assert ws(0, 128, 256, 4096, 0, 2) == bad                       # VP_SKIP_DH belongs to the backward call only
-    assert ws(2, 128, 256, 4096, 0, 2) == 128 * 4096 * 4
+    assert ws(2, 128, 256, 4096, 0, 2) == 128 * 4096 * 4 + 32 * 128 * 256 * 4
     # Algorithm 2 forward: partials + the padded bf16 softmax' operand; fp32: one [N, Vs] matrix
     assert ws(5, 4096, 4096, 4000, 1, 1) == (2 * 16 + 1) * 4096 * 4 + 4096 * 4032 * 2
-    assert ws(5, 128, 256, 4096, 0, 0) == 128 * 4096 * 4 and ws(6, 128, 256, 4096, 0, 0) == 0
+    assert ws(5, 128, 256, 4096, 0, 0) == 128 * 4096 * 4 + 32 * 128 * 256 * 4 and ws(6, 128, 256, 4096, 0, 0) == 0
     assert ws(9, 128, 256, 4096, 0, 0) == bad
     assert ws(2, 1 << 20, 256, 1 << 20, 1, 0) == bad               # N*Vs beyond 2^31 elements
 
