@@ -31,13 +31,13 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 # A plain 256 MiB copy in the same runs reads 0.5x its size on FETCH_SIZE and 1.0x on
 # WRITE_SIZE, hence the factors.  Counters cannot be read from inside this process.
 PMC_FETCH_FACTOR, PMC_WRITE_FACTOR = 2.0, 1.0
-PMC_KIB = {
-    "cfg2_llama": {"gemm_bf16_fwd_stats": (103971.6, 47143.5), "gemm_bf16_dH": (132563.4, 65536.0),
-                   "gemm_bf16_dW": (99531.9, 64000.0)},
-    "cfg3_large_vocab": {"gemm_bf16_fwd_stats": (501472.7, 157339.0), "gemm_bf16_dH": (562528.5, 65536.0),
-                         "gemm_bf16_dW": (568876.5, 256512.0)},
-    "cfg4_very_large_vocab": {"gemm_bf16_fwd_stats": (1017388.4, 28887.3), "gemm_bf16_dlogits": (1009282.2, 135936.0),
-                              "gemm_bf16_dH": (837943.6, 131073.6), "gemm_bf16_dW": (1512627.4, 512000.0)},
+PMC_KIB = {   # kernel -> (FETCH_SIZE, WRITE_SIZE); dH is the accumulating launch (7 of 8 shards; the first one writes)
+    "cfg2_llama": {"gemm_bf16_fwd_stats": (104291.8, 47158.0), "gemm_bf16_dH": (133389.5, 65536.0),
+                   "gemm_bf16_dW": (98517.4, 64000.0)},
+    "cfg3_large_vocab": {"gemm_bf16_fwd_stats": (498372.7, 165155.9), "gemm_bf16_dH": (530064.7, 65536.0),
+                         "gemm_bf16_dW": (397771.6, 256821.1)},
+    "cfg4_very_large_vocab": {"gemm_bf16_fwd_stats": (1055500.2, 29399.3), "gemm_bf16_dlogits": (1089819.0, 135955.4),
+                              "gemm_bf16_dH": (836445.1, 131323.2), "gemm_bf16_dW": (873254.6, 513676.9)},
 }
 METRIC = "vocab-layer fwd+bwd TFLOP/s and tokens/s per GPU; % of bf16 MFMA peak"
 
