@@ -118,3 +118,13 @@ def test_binding_refuses_cpu_tensors(lib):
     H = torch.zeros(8, 8)
     with pytest.raises(vp.VPError):
         vp.vp_embed_fwd(H, torch.zeros(8, dtype=torch.int64), 0, torch.zeros(8, 8))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the path runs on one GPU; asking for more must end with a message, before anything touches a GPU
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
