@@ -178,3 +178,25 @@ def test_step_can_be_captured_in_a_hip_graph():
             assert torch.equal(a, b), "replay %d differs from the eager step" % i
         plan.step()                      # eager work between replays
         torch.cuda.synchronize()
+
+
+def _random_shapes(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        p = int(rng.integers(1, 5))
+        Vs = int(rng.choice([int(rng.integers(1, 40)), int(rng.integers(40, 700)), 8 * int(rng.integers(1, 90))]))
+        h = int(rng.choice([int(rng.integers(1, 50)), 8 * int(rng.integers(1, 40)), 64 * int(rng.integers(1, 6))]))
+        N = int(rng.choice([int(rng.integers(1, 20)), int(rng.integers(20, 600))]))
+        out.append((N, h, Vs * p, p))
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_random_shapes_match_oracle(dtype):
+    # seeded draw of shapes: odd sizes, sizes below one tile, aligned and unaligned rows, both logits modes
+    for k, (N, h, V, p) in enumerate(_random_shapes(20241105, 14)):
+        H, Ws, labels = si.small_output_case(N, h, V, p, dtype, seed=900 + k, w_std=0.08)
+        for save_logits in (True, False):
+            print("random case", (N, h, V, p), save_logits, dtype, flush=True)
+            check_against_oracle(H, Ws, labels, save_logits, tag=str((N, h, V, p, save_logits, dtype)))
