@@ -3,7 +3,8 @@ bench.py times.  cfg2 is compared element by element with the full oracle.  cfg3
 large for three fp64 products and their [N, V] intermediates on the host: the oracle evaluates
 the logits and row statistics of every token over the whole vocabulary in fp64, and then the
 definitions of dH / dW on sampled token rows and sampled vocabulary rows (every sampled output
-is computed exactly as the definition states)."""
+is computed exactly as the definition states; the samples are stratified over the 256-row tiles
+of the kernels, so no output tile goes unchecked)."""
 import time
 
 import numpy as np
@@ -55,10 +56,13 @@ def _sampled_check(cfg, n_tok=48, n_voc=48):
     N, Vs, p = cfg.N, cfg.Vs, cfg.p
     X = si.as_f64(H)
     rng = np.random.default_rng(12345)
-    tok = np.sort(rng.choice(N, n_tok, replace=False))
-    # include the vocabulary rows that carry the most labels (largest one-hot contribution)
+    # stratified samples, so that every 256-row tile of dH and of every dW shard is looked at: three token
+    # rows per block of 256 tokens, one vocabulary row per block of 256 rows of every shard, plus the
+    # vocabulary rows that carry the most labels (largest one-hot contribution)
+    tok = np.sort(np.concatenate([b + rng.choice(min(256, N - b), 3, replace=False) for b in range(0, N, 256)]))
     hot = np.bincount(labels, minlength=cfg.V).argsort()[-8:]
-    voc = np.unique(np.concatenate([rng.choice(cfg.V, n_voc, replace=False), hot]))
+    strat = [r * Vs + b + int(rng.integers(0, min(256, Vs - b))) for r in range(p) for b in range(0, Vs, 256)]
+    voc = np.unique(np.concatenate([np.array(strat), rng.choice(cfg.V, n_voc, replace=False), hot]))
 
     # statistics of every token row over the whole vocabulary
     t0 = time.time()
