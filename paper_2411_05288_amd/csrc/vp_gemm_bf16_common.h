@@ -2,16 +2,16 @@
 // the four epilogues (softmax statistics of pass S, the D matrix of pass T, fp32 store and
 // fp32 accumulate).
 //
-// Accumulator layout (both kernels): 256x256 output tile per workgroup; the wavefronts form a
-// 2 x WN grid (WN = 2: four wavefronts of 128x128, WN = 4: eight wavefronts of 128x64), each
-// owning 4 x NJ tiles of the 32x32x16 bf16 MFMA (NJ = 128 / (32 WN) ... 4 or 2).  The MFMA is issued with
-// the B operand first, i.e. it produces the transposed 32x32 tile, so that register r of lane l
-// of tile (i, j) holds
+// Accumulator layout (both kernels): 256x256 output tile per workgroup of four wavefronts in a
+// 2 x 2 grid, each owning 128x128 = 4 x 4 tiles of the 32x32x16 bf16 MFMA.  (The epilogue is
+// written for a 2 x WN grid with 4 x NJ MFMA tiles per wavefront, NJ = 128 / (32 WN); the
+// kernels use WN = 2, NJ = 4.)  The MFMA is issued with the B operand first, i.e. it produces
+// the transposed 32x32 tile, so that register r of lane l of tile (i, j) holds
 //        C[ i*32 + l%32 ][ j*32 + 8*(r/4) + 4*(l/32) + r%4 ]
 // of the wavefront's block: a lane owns ONE output row per i (a token in the forward pass) and,
 // per j, four runs of four consecutive columns.  Row reductions (max / sum-exp over the
-// vocabulary) are therefore almost entirely in-register, and stores are 16 bytes (fp32) or
-// 8 bytes (bf16) per lane.
+// vocabulary) are therefore almost entirely in-register; outputs leave through an LDS staging
+// block that turns this layout into row-contiguous 16-byte stores (see gemm_epilogue).
 #pragma once
 #include "vp_internal.h"
 
