@@ -109,3 +109,8 @@ def test_cfg5_embedding_full_size():
     # the sum over shards is the plain lookup
     full_table = np.concatenate(tables)
     assert np.array_equal(total, si.bf16_bits_to_f32(full_table[ids]))
+
+
+def test_embed_more_than_65535_tokens():
+    # N above the grid.y limit and above one sorting chunk; tiny vocabulary: very long runs of equal ids
+    check_embed(70000, 8, 48, 2, "bf16", seed=72)

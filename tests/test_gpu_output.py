@@ -200,3 +200,12 @@ def test_random_shapes_match_oracle(dtype):
         for save_logits in (True, False):
             print("random case", (N, h, V, p), save_logits, dtype, flush=True)
             check_against_oracle(H, Ws, labels, save_logits, tag=str((N, h, V, p, save_logits, dtype)))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_more_than_65535_token_rows(dtype):
+    # kernels that carry the token row in grid.y work in slabs of 65535 rows; Vs = 12 keeps the
+    # elementwise D kernel on its scalar path, which is the one that slabs
+    H, Ws, labels = si.small_output_case(70000, 16, 24, 2, dtype, seed=71, w_std=0.2)
+    for save_logits in (True, False):
+        check_against_oracle(H, Ws, labels, save_logits, tag="70000 rows %s %s" % (dtype, save_logits))
