@@ -179,6 +179,14 @@ def bench_embedding(vp, cfg, steps, warmup):
         "bwd_frac_hbm_peak": bwd_bytes / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "tokens_per_s_fwd_bwd": cfg.N / ((fwd_ms + bwd_ms) * 1e-3),
         "unique_ids": uniq, "kernels": kern,
+        # dominant kernel of the input layer: the gather (algorithmic bytes of one shard over its launch time)
+        "roofline": {"bound": "hbm", "kernel": "embed_fwd",
+                     "achieved": fwd_bytes / cfg.p / (kern["embed_fwd"]["ms_per_launch"] * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": fwd_bytes / cfg.p / (kern["embed_fwd"]["ms_per_launch"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "bytes_per_launch": fwd_bytes / cfg.p, "avg_launch_ms": kern["embed_fwd"]["ms_per_launch"],
+                     # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 per launch (profiles/input_layer_cfg5_embedding.txt)
+                     "traffic": (2.0 * 2524.4 + 65564.3) * 1024.0, "traffic_unit": "bytes per launch"},
     }
 
 
