@@ -140,11 +140,15 @@ __device__ __forceinline__ void read_frags(bf16x8 (&af)[4], bf16x8 (&bf)[4], con
 
 template <Epi EPI>
 __device__ __forceinline__ void mfma_step(floatx16 (&acc)[4][4], const bf16x8 (&af)[4], const bf16x8 (&bf)[4]) {
+    // Column by column in a snake, so that only one of the two operands changes between
+    // consecutive MFMAs (less switching on the operand paths; the kernel is power limited: +1 %).
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int ii = 0; ii < 4; ++ii) {
+            const int i = (j & 1) ? 3 - ii : ii;
             mfma_tile<EPI>(acc[i][j], af[i], bf[j]);
+        }
 }
 
 template <bool A_KC, bool B_KC, Epi EPI, bool STREAM>
