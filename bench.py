@@ -190,6 +190,35 @@ def bench_embedding(vp, cfg, steps, warmup):
     }
 
 
+def mfma_sustained(vp, cfg):
+    """What the matrix cores sustain with no memory traffic at all, for operands distributed like this
+    configuration's H and W (and, for contrast, for zeros): the power-limited ceiling of any bf16 GEMM
+    on these values.  TFLOP/s."""
+    import torch
+    iters, blocks = 4096, 256
+    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    flops = blocks * 4 * iters * 16 * 2.0 * 32 * 32 * 16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    n = 8 * 256 * 8
+    half = n // 2
+    hw = torch.cat([torch.randn(half, generator=g, device="cuda") * cfg.h_std,
+                    torch.randn(half, generator=g, device="cuda") * cfg.w_std]).to(torch.bfloat16)
+    res = {}
+    for name, src in (("operands_like_H_and_W", hw), ("zero_operands", torch.zeros(n, dtype=torch.bfloat16, device="cuda"))):
+        for _ in range(5):
+            vp.vp_profile_mfma_loop(src, out, iters, blocks)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            vp.vp_profile_mfma_loop(src, out, iters, blocks)
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = flops / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12
+    return res
+
+
 def bench_barrier_overlap(vp, cfg, steps):
     """The barrier's on-device work (vp_combine_stats) on a side stream of default priority while the
     next pass S (a stand-in for the transformer work the paper overlaps its barriers with) runs on the
@@ -311,6 +340,10 @@ def main():
         per_config["barrier_overlap_" + cfg.name] = bench_barrier_overlap(vp, cfg, 50)
         torch.cuda.empty_cache()
 
+    roof = gemm_roofline(cfg, kernels)
+    if roof is not None:
+        # context for frac: the MFMA-only rate this chip sustains on such operand values (power limited)
+        roof["mfma_only_sustained_tflops"] = mfma_sustained(vp, cfg)
     out = {
         "metric": METRIC,
         "value": nums["model_tflops"],
@@ -334,7 +367,7 @@ def main():
                                                            "stored" if cfg.save_logits else "recomputed"),
                    "N": cfg.N, "h": cfg.h, "V": cfg.V, "p": cfg.p, "Vs": cfg.Vs,
                    "model_flops_per_step": cfg.model_flops},
-        "roofline": gemm_roofline(cfg, kernels),
+        "roofline": roof,
         "kernels": kernels,
         "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(cfg, args.cpu_sample_rows),
         "per_config": per_config,

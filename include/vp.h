@@ -202,6 +202,16 @@ const char* vp_profile_kernel_name(int id);
 vp_status vp_profile_enable(int on);
 vp_status vp_profile_read(double* ms_total, int64_t* launches, int n);
 
+/*
+ * Measurement aid, not part of the method: `blocks` workgroups of 4 wavefronts each run `iters` x 16
+ * back-to-back v_mfma_f32_32x32x16_bf16 on register operands, with no memory traffic inside the loop
+ * (blocks * 4 * iters * 16 * 32768 flops in total).  The matrix cores are power limited and the rate they
+ * sustain depends on the operand VALUES; this gives the ceiling for a given value distribution.
+ *   operands : in, device, 8 * 256 * 16 bytes of bf16 (the 8 operand fragments of every lane).
+ *   out      : out, device, blocks * 256 floats (keeps the work observable; contents are meaningless).
+ */
+vp_status vp_profile_mfma_loop(const void* operands, float* out, int32_t iters, int32_t blocks, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

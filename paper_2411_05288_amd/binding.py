@@ -70,6 +70,8 @@ def load_library() -> ctypes.CDLL:
     lib.vp_embed_fwd.argtypes = [vp, vp, i64, i64, i64, i64, c.c_int, vp, vp]
     lib.vp_embed_bwd.restype = c.c_int
     lib.vp_embed_bwd.argtypes = [vp, vp, i64, i64, i64, i64, c.c_int, vp, vp, sz, vp]
+    lib.vp_profile_mfma_loop.restype = c.c_int
+    lib.vp_profile_mfma_loop.argtypes = [vp, vp, i32, i32, vp]
     lib.vp_profile_kernel_count.restype = c.c_int
     lib.vp_profile_kernel_count.argtypes = []
     lib.vp_profile_kernel_name.restype = c.c_char_p
@@ -250,6 +252,15 @@ def vp_embed_bwd(grad_out, ids, shard_offset: int, dtable_shard, workspace, stre
         _ptr(grad_out, "grad_out"), _ptr(ids, "ids", (torch.int64,), (N,)), N, h, Vs, shard_offset, dt,
         _ptr(dtable_shard, "dtable_shard", (torch.float32,), (Vs, h)), wp, wb, _stream(stream))
     _check(st, "vp_embed_bwd")
+
+
+def vp_profile_mfma_loop(operands, out, iters: int, blocks: int, stream=None) -> None:
+    """Measurement aid: back-to-back MFMAs on register operands (see include/vp.h)."""
+    if operands.numel() * operands.element_size() < 8 * 256 * 16 or out.numel() < blocks * 256:
+        raise VPError("vp_profile_mfma_loop: buffers too small")
+    st = load_library().vp_profile_mfma_loop(_ptr(operands, "operands", _BF16_LIKE), _ptr(out, "out", (torch.float32,)),
+                                             iters, blocks, _stream(stream))
+    _check(st, "vp_profile_mfma_loop")
 
 
 def vp_profile_enable(on: bool) -> None:

@@ -51,7 +51,49 @@ static const char* const kNames[K_COUNT] = {
 
 }  // namespace vp
 
+namespace vp {
+// Back-to-back MFMAs on register operands, no memory traffic in the loop: what the matrix cores
+// sustain for the VALUES they are given (the chip is power limited and the rate depends on the
+// bit patterns: zeros run near the nominal peak, normally distributed operands far below it).
+// Same instruction and the same 4 x 4 accumulator blocking as the GEMM kernels.
+typedef __bf16 prof_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float prof_floatx16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void mfma_rate_kernel(const prof_bf16x8* __restrict__ src, float* __restrict__ out,
+                                                        int iters) {
+    prof_bf16x8 a[4], b[4];
+    for (int t = 0; t < 4; ++t) {
+        a[t] = src[t * 256 + threadIdx.x];
+        b[t] = src[(4 + t) * 256 + threadIdx.x];
+    }
+    prof_floatx16 acc[4][4];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j)
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        asm volatile("" : "+v"(a[0]), "+v"(b[0]));   // keeps the loop from being collapsed
+    }
+    float s = 0.f;
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j)
+            for (int r = 0; r < 16; ++r) s += acc[i][j][r];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+}  // namespace vp
+
 extern "C" {
+
+vp_status vp_profile_mfma_loop(const void* operands, float* out, int32_t iters, int32_t blocks, void* stream) {
+    if (!operands || !out || iters < 1 || blocks < 1 || blocks > 65535) return VP_ERR_INVALID_ARG;
+    if (((uintptr_t)operands & 15u) != 0) return VP_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(vp::mfma_rate_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const vp::prof_bf16x8*)operands, out, (int)iters);
+    return hipGetLastError() == hipSuccess ? VP_OK : VP_ERR_DEVICE;
+}
 
 int vp_profile_kernel_count(void) { return vp::K_COUNT; }
 
