@@ -264,3 +264,20 @@ def test_zipf_structure():
     assert 0.09 < counts.max() / 8192 < 0.17
     assert 2000 < len(counts) < 4500
     assert (si.zipf_ids(8192, 256000, 1.1, si.BASE_SEED) == ids).all()
+
+
+def test_oracle_matches_its_stored_tiny_case():
+    # tests/golden/oracle_tiny_case.json is written by tests/golden/make_oracle_golden.py (oracle only);
+    # it guards the oracle's arithmetic against silent change
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_oracle_golden", os.path.join(here, "golden", "make_oracle_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.compute()
+    stored = json.load(open(os.path.join(here, "golden", "oracle_tiny_case.json")))
+    assert now["labels"] == stored["labels"] and now["ids"] == stored["ids"]
+    for k in ("loss", "m", "sum", "m_loc", "sum_loc", "dX", "dW_shard1", "alg2_dX", "alg2_A0", "embed_bwd_shard1"):
+        np.testing.assert_allclose(np.asarray(now[k]), np.asarray(stored[k]), rtol=1e-12, atol=1e-15, err_msg=k)
