@@ -211,20 +211,28 @@ __device__ __forceinline__ void add_grad(float (&acc)[4], const float4& v, bool 
 }
 __device__ __forceinline__ void add_grad(float (&acc)[1], const float& v, bool on) { acc[0] += gate(v, on); }
 
-// Adds tokens u0 .. min(u0 + D, cnt) - 1 of the 64 whose positions sit in the lanes of `tok`:
-// D loads issued back to back, then D adds in order.  No branches: positions past cnt re-read
-// the last valid row and add -0.0f.
-template <int D, int VEC, typename GV, typename T>
-__device__ __forceinline__ void accum_batch(float (&acc)[VEC], const T* gcol, int h, unsigned tok, int u0, int cnt) {
-    GV v[D];
+// Loads of tokens u0 .. u0 + D - 1 of the 64 whose positions sit in the lanes of `tok`, issued
+// back to back.  No branches: positions past cnt re-read the last valid row.
+template <int D, typename GV, typename T>
+__device__ __forceinline__ void load_batch(GV (&v)[D], const T* gcol, int h, unsigned tok, int u0, int cnt) {
 #pragma unroll
     for (int u = 0; u < D; ++u) {
         const int idx = (u0 + u < cnt) ? (u0 + u) : (cnt - 1);
         const unsigned t = __builtin_amdgcn_readlane(tok, idx);
         v[u] = *reinterpret_cast<const GV*>(gcol + (size_t)t * h);
     }
+}
+// The adds of those tokens in order; positions past cnt add -0.0f.
+template <int D, int VEC, typename GV>
+__device__ __forceinline__ void add_batch(float (&acc)[VEC], const GV (&v)[D], int u0, int cnt) {
 #pragma unroll
     for (int u = 0; u < D; ++u) add_grad(acc, v[u], u0 + u < cnt);
+}
+template <int D, int VEC, typename GV, typename T>
+__device__ __forceinline__ void accum_batch(float (&acc)[VEC], const T* gcol, int h, unsigned tok, int u0, int cnt) {
+    GV v[D];
+    load_batch<D>(v, gcol, h, tok, u0, cnt);
+    add_batch<D, VEC>(acc, v, u0, cnt);
 }
 
 template <typename T, int VEC>
@@ -254,19 +262,31 @@ __global__ __launch_bounds__(256) void embed_bwd_accum_kernel(const u64* __restr
     }
     const T* gcol = gout + (active ? c0 : 0);
 
+    // 64 keys of the run per wavefront-wide load; the keys of the next 64 positions are fetched
+    // before this chunk is worked on, so a long run pays one memory latency per 64 tokens (its
+    // 64 row loads, all in flight together) instead of three (keys, then two batches of 32)
+    u64 kq = (s + lane < n_pad) ? keys[s + lane] : KEY_NONE;
     for (int q0 = s; q0 < n_pad; q0 += 64) {
-        // 64 keys of the run per wavefront-wide load; cnt = how many of them continue the run
-        const u64 kq = (q0 + lane < n_pad) ? keys[q0 + lane] : KEY_NONE;
+        const u64 kq_next = (q0 + 64 + lane < n_pad) ? keys[q0 + 64 + lane] : KEY_NONE;
         const bool same = (kq != KEY_NONE) && ((unsigned)(kq >> 32) == row);
         const u64 m = __builtin_amdgcn_ballot_w64(same);
-        const int cnt = (m == ~0ull) ? 64 : __builtin_ctzll(~m);
+        const int cnt = (m == ~0ull) ? 64 : __builtin_ctzll(~m);   // how many of them continue the run
         const unsigned tok = (unsigned)kq;
         if (active) {
-            int u0 = 0;
-            for (; u0 + DEPTH <= cnt; u0 += DEPTH) accum_batch<DEPTH, VEC, GV>(acc, gcol, h, tok, u0, cnt);
-            for (; u0 < cnt; u0 += 4) accum_batch<4, VEC, GV>(acc, gcol, h, tok, u0, cnt);
+            if (cnt == 64) {
+                GV v0[DEPTH], v1[DEPTH];
+                load_batch<DEPTH>(v0, gcol, h, tok, 0, 64);
+                load_batch<DEPTH>(v1, gcol, h, tok, DEPTH, 64);
+                add_batch<DEPTH, VEC>(acc, v0, 0, 64);
+                add_batch<DEPTH, VEC>(acc, v1, DEPTH, 64);
+            } else {
+                int u0 = 0;
+                for (; u0 + DEPTH <= cnt; u0 += DEPTH) accum_batch<DEPTH, VEC, GV>(acc, gcol, h, tok, u0, cnt);
+                for (; u0 < cnt; u0 += 4) accum_batch<4, VEC, GV>(acc, gcol, h, tok, u0, cnt);
+            }
         }
         if (cnt < 64) break;
+        kq = kq_next;
     }
     if (active) {
         if (VEC == 4) {
