@@ -25,7 +25,7 @@
  *   - Labels / token ids are global vocabulary ids (int64).  An id outside the shard's
  *     range [shard_offset, shard_offset + Vs) - including ids outside [0, V) - is treated
  *     as "not owned": target logit 0, all-zero one-hot row, zero output row, no scatter.
- *   - Sizes: 1 <= N, h, Vs and N*Vs, N*h, Vs*h < 2^31 elements each.
+ *   - Sizes: 1 <= N, h, Vs; h, Vs <= 2^20; and N*Vs, N*h, Vs*h < 2^31 elements each.
  */
 #ifndef VP_H_
 #define VP_H_

@@ -12,8 +12,11 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 bool sizes_ok(int64_t N, int64_t h, int64_t Vs) { return N >= 1 && h >= 1 && Vs >= 1; }
 
+// Row lengths are limited to 2^20 elements: the GEMM epilogues address 256 rows of an output with 32-bit byte offsets.
+constexpr int64_t MAX_ROW = (int64_t)1 << 20;
+
 bool sizes_supported(int64_t N, int64_t h, int64_t Vs) {
-    return N < MAX_ELEMS && h < MAX_ELEMS && Vs < MAX_ELEMS && N * Vs < MAX_ELEMS && N * h < MAX_ELEMS &&
+    return N < MAX_ELEMS && h <= MAX_ROW && Vs <= MAX_ROW && N * Vs < MAX_ELEMS && N * h < MAX_ELEMS &&
            Vs * h < MAX_ELEMS;
 }
 

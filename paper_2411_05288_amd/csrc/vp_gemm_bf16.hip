@@ -121,6 +121,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(GemmBf16Params g) {
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    if (EPI == Epi::FwdStats && n0 + BN > g.N) init_acc_ragged<4, 2>(acc, g.N, tile_n);
 
     uint4 ra[8], rb[8];
     const int nkt = (g.K + BK - 1) / BK;
@@ -172,6 +173,10 @@ static hipError_t launch_t(const GemmBf16Params& p, hipStream_t st) {
 
 hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st) {
     if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
+    // the epilogue addresses the 256 rows of an output tile with 32-bit byte offsets
+    const bool f32_out = p.epi == Epi::StoreF32 || p.epi == Epi::AccumF32;
+    if (f32_out ? (long long)p.ldc * 4 > EPI_MAX_ROW_BYTES : (p.Y && (long long)p.ldy * 2 > EPI_MAX_ROW_BYTES))
+        return hipErrorInvalidValue;
     const int kid = p.kernel_id ? p.kernel_id
                   : p.epi == Epi::FwdStats ? K_GEMM_FWD_STATS
                   : p.epi == Epi::DLogits  ? K_GEMM_DLOGITS

@@ -13,6 +13,8 @@
 // vocabulary) are therefore almost entirely in-register; outputs leave through an LDS staging
 // block that turns this layout into row-contiguous 16-byte stores (see gemm_epilogue).
 #pragma once
+
+#include <type_traits>
 #include "vp_internal.h"
 
 namespace vp {
@@ -42,6 +44,27 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 template <Epi EPI>
 __device__ __forceinline__ void mfma_tile(floatx16& c, const bf16x8& a, const bf16x8& b) {
     c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c, 0, 0, 0);
+}
+
+// Pass S, ragged last column tile: the accumulators of the columns past the end of the shard are
+// set to -inf before the main loop (the others hold zero).  Their products are exactly zero (rows of
+// W past the end are read as zeros), so they stay -inf: they leave the row maximum alone and add
+// exp(-inf) = 0 to the sum, with no masking pass over the accumulators in the epilogue.  Written
+// straight into the AGPR half of the register file, like the zeros.
+template <int NJ, int WN>
+__device__ __forceinline__ void init_acc_ragged(floatx16 (&acc)[4][NJ], int n_cols, int tile_n) {
+    const int lane = threadIdx.x & 63;
+    const int wn = (threadIdx.x >> 6) % WN;
+    // this lane holds columns cbase + j*32 + 8*(r/4) + r%4; those below nvalid exist
+    const int nvalid = n_cols - (tile_n * BN + wn * (NJ * 32) + 4 * (lane >> 5));
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float z = (j * 32 + 8 * (r >> 2) + (r & 3) < nvalid) ? 0.f : -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { float t; asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(t) : "v"(z)); acc[i][j][r] = t; }
+        }
 }
 
 // Virtual workgroup id -> output tile.  v = round * nb + b with nb workgroups per round (one
@@ -157,31 +180,46 @@ struct StageBf16 {
     static constexpr int STEPS = 32 / RPI;
 };
 
+// Output tiles are stored through a raw buffer descriptor that covers exactly the tile's rows
+// (all columns): a lane whose row lies past the end of the matrix then has an offset beyond the
+// buffer and the hardware drops its store (a load returns zero), and a lane whose 16-byte chunk
+// lies past the last column is given the offset OOB_OFFSET, beyond any such buffer.  This keeps
+// the epilogue free of branches: with a branch per store, every store would be followed by a
+// full wait on the memory counter (which counts stores as well) and the stores would go out one
+// acknowledgement at a time.  The host checks that 256 rows of the output stay below 2 GB.
+constexpr unsigned OOB_OFFSET = 0x80000000u;
+constexpr long long EPI_MAX_ROW_BYTES = (1ll << 31) / 256;   // limit on ld * sizeof(element) of an output
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rows_rsrc(void* first_row, int rows, unsigned row_bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(first_row, 0, (int)((unsigned)rows * row_bytes), 0x00020000);
+}
+
 // Wavefront-private staging block -> global memory, bf16: 16 bytes per lane, row-contiguous.
+// `off` is the lane's byte offset of staged row `orow` (or beyond the buffer, see above).
 template <typename St, bool STREAM>
-__device__ __forceinline__ void flush_stage_bf16(const char* region, u16* Y, int ldy, int row_first, int M, int ocol,
-                                                 int N, bool vec, bool interior, int orow, int ochunk) {
-    if (interior) {
-        uintx4 v[St::STEPS];
+__device__ __forceinline__ void flush_stage_bf16(const char* region, __amdgpu_buffer_rsrc_t rs, unsigned off,
+                                                 unsigned row_bytes, int orow, int ochunk) {
+    // the staged rows are all fetched first, then stored back to back
+    uintx4 v[St::STEPS];
 #pragma unroll
-        for (int s = 0; s < St::STEPS; ++s)
-            v[s] = *reinterpret_cast<const uintx4*>(region + (s * St::RPI + orow) * St::RS + ochunk * 16);
+    for (int s = 0; s < St::STEPS; ++s)
+        v[s] = *reinterpret_cast<const uintx4*>(region + (s * St::RPI + orow) * St::RS + ochunk * 16);
 #pragma unroll
-        for (int s = 0; s < St::STEPS; ++s) asm volatile("" : "+v"(v[s]));
+    for (int s = 0; s < St::STEPS; ++s) asm volatile("" : "+v"(v[s]));
 #pragma unroll
-        for (int s = 0; s < St::STEPS; ++s)
-        {
-            uintx4* dst = reinterpret_cast<uintx4*>(Y + (size_t)(row_first + s * St::RPI + orow) * ldy + ocol);
-            if (STREAM) __builtin_nontemporal_store(v[s], dst);
-            else *dst = v[s];
-        }
-    } else {
+    for (int s = 0; s < St::STEPS; ++s)
+        __builtin_amdgcn_raw_buffer_store_b128(v[s], rs, (int)(off + (unsigned)(s * St::RPI) * row_bytes), 0, STREAM ? 2 : 0);
+}
+
+// The same for outputs whose rows are not 16-byte aligned (or whose last column cuts a chunk).
+template <typename St>
+__device__ __forceinline__ void flush_stage_bf16_unaligned(const char* region, u16* Y, int ldy, int row_first, int M,
+                                                           int ocol, int N, bool aligned, int orow, int ochunk) {
 #pragma unroll
-        for (int s = 0; s < St::STEPS; ++s) {
-            const int rr = s * St::RPI + orow;
-            const uint4 v = *reinterpret_cast<const uint4*>(region + rr * St::RS + ochunk * 16);
-            if (row_first + rr < M) store8_bf16(Y + (size_t)(row_first + rr) * ldy, ocol, N, vec, v);
-        }
+    for (int s = 0; s < St::STEPS; ++s) {
+        const int rr = s * St::RPI + orow;
+        const uint4 v = *reinterpret_cast<const uint4*>(region + rr * St::RS + ochunk * 16);
+        if (row_first + rr < M) store8_bf16(Y + (size_t)(row_first + rr) * ldy, ocol, N, aligned, v);
     }
 }
 
@@ -193,8 +231,8 @@ __device__ __forceinline__ void flush_stage_bf16(const char* region, u16* Y, int
 // four tiles per workgroup, -1.6 % with one; the launcher picks by tiles per workgroup).  A
 // compile-time choice: two stores that differ only in that hint get merged into a plain one.
 template <Epi EPI, int NJ, int WN, bool STREAM>
-__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const GemmBf16Params& g, int tile_m, int tile_n,
-                                              char* xchg, char* region) {
+__device__ __forceinline__ void gemm_epilogue_f32(floatx16 (&acc)[4][NJ], const GemmBf16Params& g, int tile_m, int tile_n,
+                                                  char* region) {
     constexpr int WCOLS = NJ * 32;            // columns owned by one wavefront
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -202,9 +240,6 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, hf = lane >> 5;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    // element (i, j, r) of this lane: row = rbase + i*32, col = cbase + j*32 + 8*(r/4) + (r%4)
-    const int rbase = m0 + wm * 128 + l32;
-    const int cbase = n0 + wn * WCOLS + 4 * hf;
 
     if (EPI == Epi::StoreF32 || EPI == Epi::AccumF32) {
         typedef StageF32<WCOLS> St;
@@ -273,48 +308,107 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
             wave_lds_fence();
         }
     }
+}
+
+// The epilogues of pass S (FwdStats) and of the fused pass T (DLogits): bf16 outputs.
+template <Epi EPI, int NJ, int WN, bool STREAM>
+__device__ __forceinline__ void gemm_epilogue_bf16(floatx16 (&acc)[4][NJ], const GemmBf16Params& g, int tile_m, int tile_n,
+                                                   char* xchg, char* region) {
+    constexpr int WCOLS = NJ * 32;            // columns owned by one wavefront
+    // Arithmetic on threadIdx does not depend on the tile, so it is hoisted above the caller's tile
+    // loop and main loop, where it occupies (and spills) registers; a reload from the spill area after
+    // the first output stores would moreover wait for those stores to be acknowledged (a reload is a
+    // load).  These epilogues are short of registers, so they take the lane index from the hardware's
+    // lane count and make it opaque: what follows is computed here, per tile.
+    int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(lane));
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tid = wave * 64 + lane;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l32 = lane & 31, hf = lane >> 5;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    // element (i, j, r) of this lane: row = rbase + i*32, col = cbase + j*32 + 8*(r/4) + (r%4)
+    const int rbase = m0 + wm * 128 + l32;
+    const int cbase = n0 + wn * WCOLS + 4 * hf;
 
     if (EPI == Epi::DLogits) {
         // D = (softmax - G) * scale with the global statistics (pass T of Algorithm 1, with
         // the logits taken from the accumulators instead of memory)
         typedef StageBf16<WCOLS> St;
-        const bool vec = (g.ldy % 8 == 0) && (((uintptr_t)g.Y & 15u) == 0);
-        const bool interior = vec && (m0 + BM <= g.M) && (n0 + BN <= g.N);   // uniform over the workgroup
+        // uniform over the grid: rows are 16-byte aligned and chunks are never cut by the last column
+        const bool aligned = (g.ldy % 8 == 0) && (((uintptr_t)g.Y & 15u) == 0);
+        const bool vec = aligned && (g.N % 8 == 0);
         const int orow = lane / St::LPR, ochunk = lane % St::LPR;
         const int ocol = n0 + wn * WCOLS + ochunk * 8;
+        const unsigned row_bytes = (unsigned)g.ldy * 2u;
+        const __amdgpu_buffer_rsrc_t rs =
+            tile_rows_rsrc(g.Y + (size_t)m0 * g.ldy, g.M - m0 < BM ? g.M - m0 : BM, row_bytes);
+        const unsigned off0 =
+            (ocol + 8 <= g.N) ? (unsigned)(wm * 128 + orow) * row_bytes + (unsigned)ocol * 2u : OOB_OFFSET;
+        // all loads come before the first store (see the note on the labels in the FwdStats branch)
+        float ml2_[4], f_[4];
+        int lab_[4];
+        {
+            float gm[4], gs[4];
+            int64_t lraw[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = rbase + i * 32;
-            const int rowc = row < g.M ? row : g.M - 1;      // rows past the end compute on a copy, store nothing
-            const float m = g.gmax[rowc];
-            const float inv = 1.0f / g.gsum[rowc];
-            const int64_t lab64 = g.labels[rowc] - g.shard_offset - cbase;
-            // column of the label relative to cbase, or -1 when it is not in this lane's range
-            const int lab = (lab64 >= 0 && lab64 < WCOLS) ? (int)lab64 : -1;
-            const float ml2 = m * LOG2E;
-            const float f = inv * g.scale;
-            // the one-hot term touches at most one element per row: a wavefront-uniform branch
-            // keeps the 64 compares out of the common case
-            const bool any_label = __builtin_amdgcn_ballot_w64(lab >= 0) != 0;
+            for (int i = 0; i < 4; ++i) {
+                const int row = rbase + i * 32;
+                const int rowc = row < g.M ? row : g.M - 1;      // rows past the end compute on a copy, store nothing
+                gm[i] = g.gmax[rowc];
+                gs[i] = g.gsum[rowc];
+                lraw[i] = g.labels[rowc];
+            }
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float d[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) d[e] = exp2_fast(fmaf(acc[i][j][4 * q + e], LOG2E, -ml2)) * f;
-                    if (any_label) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (lab == j * 32 + 8 * q + e) d[e] -= g.scale;
-                    }
-                    *reinterpret_cast<uint2*>(region + l32 * St::RS + (j * 32 + 8 * q + 4 * hf) * 2) =
-                        make_uint2(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]));
-                }
-            wave_lds_fence();
-            flush_stage_bf16<St, STREAM>(region, g.Y, g.ldy, m0 + wm * 128 + i * 32, g.M, ocol, g.N, vec, interior, orow, ochunk);
-            wave_lds_fence();
+            for (int i = 0; i < 4; ++i) {
+                const int64_t lab64 = lraw[i] - g.shard_offset - cbase;
+                // column of the label relative to cbase, or -1 when it is not in this lane's range
+                lab_[i] = (lab64 >= 0 && lab64 < WCOLS) ? (int)lab64 : -1;
+                ml2_[i] = gm[i] * LOG2E;
+                f_[i] = (1.0f / gs[i]) * g.scale;
+            }
+            // keep the derived values, not the inputs
+            asm volatile("" : "+v"(lab_[0]), "+v"(lab_[1]), "+v"(lab_[2]), "+v"(lab_[3]));
+            asm volatile("" : "+v"(ml2_[0]), "+v"(ml2_[1]), "+v"(ml2_[2]), "+v"(ml2_[3]));
+            asm volatile("" : "+v"(f_[0]), "+v"(f_[1]), "+v"(f_[2]), "+v"(f_[3]));
         }
+        auto blocks = [&](auto vec_c) {
+            constexpr bool VEC = decltype(vec_c)::value;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                // One row block at a time: left alone, the scheduler uses every free register to overlap the
+                // blocks and then spills, and a reload after the first stores waits for them (a reload is a load).
+                __builtin_amdgcn_sched_barrier(0);
+                const int lab = lab_[i];
+                const float ml2 = ml2_[i];
+                const float f = f_[i];
+                // the one-hot term touches at most one element per row: a wavefront-uniform branch
+                // keeps the 64 compares out of the common case
+                const bool any_label = __builtin_amdgcn_ballot_w64(lab >= 0) != 0;
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float d[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) d[e] = exp2_fast(fmaf(acc[i][j][4 * q + e], LOG2E, -ml2)) * f;
+                        if (any_label) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (lab == j * 32 + 8 * q + e) d[e] -= g.scale;
+                        }
+                        *reinterpret_cast<uint2*>(region + l32 * St::RS + (j * 32 + 8 * q + 4 * hf) * 2) =
+                            make_uint2(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]));
+                    }
+                wave_lds_fence();
+                if (VEC) flush_stage_bf16<St, STREAM>(region, rs, off0 + (unsigned)(i * 32) * row_bytes, row_bytes, orow, ochunk);
+                else flush_stage_bf16_unaligned<St>(region, g.Y, g.ldy, m0 + wm * 128 + i * 32, g.M, ocol, g.N, aligned, orow, ochunk);
+                wave_lds_fence();
+            }
+        };
+        // (chosen once, outside the loop: see the fp32 branch above)
+        if (vec) blocks(std::true_type{});
+        else blocks(std::false_type{});
     }
 
     if (EPI == Epi::FwdStats) {
@@ -326,24 +420,32 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
         typedef StageBf16<WCOLS> St;
         float* xm = reinterpret_cast<float*>(xchg);          // [WN][256]
         float* xs = xm + WN * 256;                             // [WN][256]
-        const bool vec = g.Y && (g.ldy % 8 == 0) && (((uintptr_t)g.Y & 15u) == 0);
-        const bool interior = vec && (m0 + BM <= g.M) && (n0 + BN <= g.N);   // uniform over the workgroup
+        // uniform over the grid: rows are 16-byte aligned and chunks are never cut by the last column
+        const bool aligned = g.Y && (g.ldy % 8 == 0) && (((uintptr_t)g.Y & 15u) == 0);
+        const bool vec = aligned && (g.N % 8 == 0);
         const int orow = lane / St::LPR, ochunk = lane % St::LPR;
         const int ocol = n0 + wn * WCOLS + ochunk * 8;
-        if (n0 + BN > g.N) {
-            // ragged last column tile: columns past the shard take -inf, which leaves the
-            // maximum alone and adds exp(-inf) = 0 to the sum
+        const unsigned row_bytes = (unsigned)g.ldy * 2u;
+        const __amdgpu_buffer_rsrc_t rs =
+            tile_rows_rsrc(g.Y ? g.Y + (size_t)m0 * g.ldy : nullptr, g.Y ? (g.M - m0 < BM ? g.M - m0 : BM) : 0, row_bytes);
+        const unsigned off0 =
+            (ocol + 8 <= g.N) ? (unsigned)(wm * 128 + orow) * row_bytes + (unsigned)ocol * 2u : OOB_OFFSET;
+        // The labels of the wavefront's four row blocks are fetched before the first store of
+        // logits: the memory counter a load is waited on also counts the stores issued before it,
+        // so a load inside the loop below would wait for the previous block's stores to be
+        // acknowledged and serialise the epilogue.
+        int64_t lraw[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (cbase + j * 32 + 8 * (r >> 2) + (r & 3) >= g.N) acc[i][j][r] = -INFINITY;
-        }
+        for (int i = 0; i < 4; ++i) lraw[i] = (rbase + i * 32 < g.M) ? g.labels[rbase + i * 32] : (int64_t)-1;
+        // lab[i]: column of row block i's label relative to cbase if this lane holds it, else -1
+        int lab[4];
+        // (columns past the shard in the ragged last column tile hold -inf: see init_acc)
+        // MODE 0: the logits are not kept; 1: stored through the tile's buffer descriptor; 2: unaligned rows
+        auto blocks = [&](auto mode_c) {
+        constexpr int MODE = decltype(mode_c)::value;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int row = rbase + i * 32;
+            __builtin_amdgcn_sched_barrier(0);          // one row block at a time (see the DLogits branch)
             float v = acc[i][0][0];
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
@@ -364,22 +466,27 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
                 xm[wn * 256 + lr] = m;
                 xs[wn * 256 + lr] = s;
             }
-            {
-                const int64_t lab64 = (row < g.M ? g.labels[row] : (int64_t)-1) - g.shard_offset - cbase;
-                const bool mine = row < g.M && lab64 >= 0 && lab64 < WCOLS && (lab64 & 4) == 0 && lab64 + cbase < g.N;
-                // at most one element per row is a target logit: wavefront-uniform branch
-                if (__builtin_amdgcn_ballot_w64(mine) != 0) {
-                    const int lab = mine ? (int)lab64 : -1;
-                    float t = 0.f;
+            if (i == 0) {
+                // the four loads have had the first block's arithmetic to arrive
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (lab == j * 32 + 8 * (r >> 2) + (r & 3)) t = acc[i][j][r];
-                    if (mine) g.part_tgt[row] = t;
+                for (int k = 0; k < 4; ++k) {
+                    const int64_t lab64 = lraw[k] - g.shard_offset - cbase;
+                    const bool mine = lraw[k] >= 0 && lab64 >= 0 && lab64 < WCOLS && (lab64 & 4) == 0 && lab64 + cbase < g.N;
+                    lab[k] = mine ? (int)lab64 : -1;
                 }
+                asm volatile("" : "+v"(lab[0]), "+v"(lab[1]), "+v"(lab[2]), "+v"(lab[3]));   // narrowed here, not at the use
             }
-            if (g.Y) {
+            // at most one element per row is a target logit: wavefront-uniform branch
+            if (__builtin_amdgcn_ballot_w64(lab[i] >= 0) != 0) {
+                float t = 0.f;
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (lab[i] == j * 32 + 8 * (r >> 2) + (r & 3)) t = acc[i][j][r];
+                if (lab[i] >= 0) g.part_tgt[rbase + i * 32] = t;
+            }
+            if (MODE != 0) {
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
 #pragma unroll
@@ -388,10 +495,16 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
                             make_uint2(pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]),
                                        pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
                 wave_lds_fence();
-                flush_stage_bf16<St, STREAM>(region, g.Y, g.ldy, m0 + wm * 128 + i * 32, g.M, ocol, g.N, vec, interior, orow, ochunk);
+                if (MODE == 1) flush_stage_bf16<St, STREAM>(region, rs, off0 + (unsigned)(i * 32) * row_bytes, row_bytes, orow, ochunk);
+                else flush_stage_bf16_unaligned<St>(region, g.Y, g.ldy, m0 + wm * 128 + i * 32, g.M, ocol, g.N, aligned, orow, ochunk);
                 wave_lds_fence();
             }
         }
+        };
+        // (chosen once, outside the loop: see the fp32 branch above)
+        if (!g.Y) blocks(std::integral_constant<int, 0>{});
+        else if (vec) blocks(std::integral_constant<int, 1>{});
+        else blocks(std::integral_constant<int, 2>{});
         __syncthreads();
         if (tid < 256) {
             const int row = m0 + tid;
@@ -410,6 +523,15 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const Gemm
             }
         }
     }
+}
+
+template <Epi EPI, int NJ, int WN, bool STREAM>
+__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[4][NJ], const GemmBf16Params& g, int tile_m, int tile_n,
+                                              char* xchg, char* region) {
+    if constexpr (EPI == Epi::StoreF32 || EPI == Epi::AccumF32)
+        gemm_epilogue_f32<EPI, NJ, WN, STREAM>(acc, g, tile_m, tile_n, region);
+    else
+        gemm_epilogue_bf16<EPI, NJ, WN, STREAM>(acc, g, tile_m, tile_n, xchg, region);
 }
 
 }  // namespace vp

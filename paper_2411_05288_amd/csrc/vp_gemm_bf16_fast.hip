@@ -189,6 +189,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { float z; asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(z)); acc[i][j][r] = z; }
+    if (EPI == Epi::FwdStats && n0 + BN > g.N) init_acc_ragged<4, 2>(acc, g.N, tile_n);
 
     unsigned avoff[8], bvoff[8];
     tile_voffsets<A_KC>(avoff, m0, g.lda, wave, lane);

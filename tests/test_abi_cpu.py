@@ -70,6 +70,8 @@ def test_workspace_sizes(lib):
     assert ws(5, 128, 256, 4096, 0, 0) == 128 * 4096 * 4 + 32 * 128 * 256 * 4 and ws(6, 128, 256, 4096, 0, 0) == 0
     assert ws(9, 128, 256, 4096, 0, 0) == bad
     assert ws(2, 1 << 20, 256, 1 << 20, 1, 0) == bad               # N*Vs beyond 2^31 elements
+    assert ws(0, 8, 8, (1 << 20) + 8, 1, 0) == bad and ws(0, 8, 8, 1 << 20, 1, 0) != bad   # rows of at most 2^20 elements
+    assert ws(2, 8, (1 << 20) + 8, 8, 1, 0) == bad
 
 
 def test_argument_validation_launches_nothing(lib):
