@@ -209,3 +209,53 @@ def test_more_than_65535_token_rows(dtype):
     H, Ws, labels = si.small_output_case(70000, 16, 24, 2, dtype, seed=71, w_std=0.2)
     for save_logits in (True, False):
         check_against_oracle(H, Ws, labels, save_logits, tag="70000 rows %s %s" % (dtype, save_logits))
+
+
+def _guarded(shape, dtype, fill, guard=4096):
+    """A contiguous tensor of `shape` cut from the middle of a larger buffer filled with `fill`."""
+    n = int(np.prod(shape))
+    big = torch.full((n + 2 * guard,), fill, dtype=dtype, device="cuda")
+    return big, big[guard:guard + n].view(*shape), guard
+
+
+@pytest.mark.parametrize("shape", [
+    # N,   h,   Vs:  every output tile is ragged in rows and columns
+    (300, 128, 1000),     # 16-byte aligned rows everywhere: the descriptor-bounded store path
+    (257, 64, 264),       # one row past a row tile, 8 columns past a column tile
+    (513, 72, 250),       # rows of the logits / D not 16-byte aligned: the element-wise store path
+])
+@pytest.mark.parametrize("save_logits", [True, False])
+def test_nothing_is_written_outside_the_output_extents(shape, save_logits):
+    # the GEMM epilogues store through descriptors sized to the tile's rows and rely on the hardware
+    # dropping what lies beyond; every output sits between guard bands that must keep their fill,
+    # and so must the workspace beyond the size the library asks for
+    import paper_2411_05288_amd as vp
+    N, h, Vs = shape
+    H, Ws, labels = si.small_output_case(N, h, Vs, 1, "bf16", seed=91)
+    Hd, Wd, ld = to_dev(H), to_dev(Ws[0]), to_dev(labels)
+    f32, bf16 = torch.float32, torch.bfloat16
+    flags = vp.VP_SAVE_LOGITS if save_logits else 0
+    need = max(vp.vp_workspace_bytes(vp.binding.VP_CALL_OUTPUT_FWD, N, h, Vs, vp.VP_BF16, flags),
+               vp.vp_workspace_bytes(vp.binding.VP_CALL_OUTPUT_BWD, N, h, Vs, vp.VP_BF16, flags), 256)
+    ws_big = torch.full((need + 8192,), 0x5A, dtype=torch.uint8, device="cuda")
+    bufs = {}
+    for name, shp, dt, fill in [("lm", (N,), f32, 7.0), ("ls", (N,), f32, 7.0), ("lt", (N,), f32, 7.0),
+                                ("logits", (N, Vs), bf16, 7.0), ("dH", (N, h), f32, 7.0), ("dW", (Vs, h), f32, 7.0)]:
+        bufs[name] = _guarded(shp, dt, fill)
+    t = {k: v[1] for k, v in bufs.items()}
+    vp.vp_output_fwd(Hd, Wd, ld, 0, t["lm"], t["ls"], t["lt"], t["logits"] if save_logits else None, ws_big[:need])
+    t["dH"].zero_()
+    vp.vp_output_bwd(Hd, Wd, ld, 0, t["lm"].clone(), t["ls"].clone(), t["logits"] if save_logits else None, 1.0 / N,
+                     t["dH"], t["dW"], ws_big[:need])
+    torch.cuda.synchronize()
+    for name, (big, view, guard) in bufs.items():
+        assert bool((big[:guard] == 7.0).all()) and bool((big[guard + view.numel():] == 7.0).all()), \
+            "%s: written outside its extent" % name
+    assert bool((ws_big[need:] == 0x5A).all()), "workspace written beyond the size vp_workspace_bytes returned"
+    # and what is inside is right: one shard, so the local statistics are the global ones
+    ref = oc.output_layer(si.as_f64(H), si.as_f64(Ws[0]), labels)
+    assert rel_max_err(to_host(t["dH"]).astype(np.float64), ref["dX"]) <= GRAD_TOL["bf16"]
+    assert rel_max_err(to_host(t["dW"]).astype(np.float64), ref["dW"]) <= GRAD_TOL["bf16"]
+    if save_logits:
+        y = to_host_f64(t["logits"])
+        assert np.abs(y - ref["Y"]).max() <= (2.0 ** -8) * np.abs(ref["Y"]).max() + 1e-6
