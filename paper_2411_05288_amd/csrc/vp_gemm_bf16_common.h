@@ -241,77 +241,75 @@ __device__ __forceinline__ void gemm_epilogue_f32(floatx16 (&acc)[4][NJ], const 
     const int l32 = lane & 31, hf = lane >> 5;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    if (EPI == Epi::StoreF32 || EPI == Epi::AccumF32) {
-        typedef StageF32<WCOLS> St;
-        constexpr bool ACCUM = (EPI == Epi::AccumF32);
-        const bool vec = (g.ldc % 4 == 0) && (((uintptr_t)g.C & 15u) == 0);
-        const int orow = lane / St::LPR, ochunk = lane % St::LPR;
-        const int col = n0 + wn * WCOLS + ochunk * 4;
-        const bool interior = vec && (m0 + BM <= g.M) && (n0 + BN <= g.N);   // uniform over the workgroup
-        // accumulators of row block i -> the wavefront's staging block
-        auto stage = [&](int i) {
+    typedef StageF32<WCOLS> St;
+    constexpr bool ACCUM = (EPI == Epi::AccumF32);
+    const bool vec = (g.ldc % 4 == 0) && (((uintptr_t)g.C & 15u) == 0);
+    const int orow = lane / St::LPR, ochunk = lane % St::LPR;
+    const int col = n0 + wn * WCOLS + ochunk * 4;
+    const bool interior = vec && (m0 + BM <= g.M) && (n0 + BN <= g.N);   // uniform over the workgroup
+    // accumulators of row block i -> the wavefront's staging block
+    auto stage = [&](int i) {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const floatx4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                    *reinterpret_cast<floatx4*>(region + l32 * St::RS + (j * 32 + 8 * q + 4 * hf) * 4) = v;
-                }
-        };
-        if (interior) {
-            // Whole tile inside the matrix: straight-line code.  The old values of C are fetched one row
-            // block ahead, before the previous block's stores: the memory counter a load is waited on also
-            // counts the stores issued before it, so waiting for loads issued after a block's stores would
-            // mean waiting for those stores to be acknowledged.
-            float* c0 = g.C + (size_t)(m0 + wm * 128 + orow) * g.ldc + col;
-            auto c_at = [&](int i, int s) { return reinterpret_cast<floatx4*>(c0 + (size_t)(i * 32 + s * St::RPI) * g.ldc); };
-            floatx4 cv[St::STEPS];
+            for (int q = 0; q < 4; ++q) {
+                const floatx4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                *reinterpret_cast<floatx4*>(region + l32 * St::RS + (j * 32 + 8 * q + 4 * hf) * 4) = v;
+            }
+    };
+    if (interior) {
+        // Whole tile inside the matrix: straight-line code.  The old values of C are fetched one row
+        // block ahead, before the previous block's stores: the memory counter a load is waited on also
+        // counts the stores issued before it, so waiting for loads issued after a block's stores would
+        // mean waiting for those stores to be acknowledged.
+        float* c0 = g.C + (size_t)(m0 + wm * 128 + orow) * g.ldc + col;
+        auto c_at = [&](int i, int s) { return reinterpret_cast<floatx4*>(c0 + (size_t)(i * 32 + s * St::RPI) * g.ldc); };
+        floatx4 cv[St::STEPS];
+        if (ACCUM) {
+#pragma unroll
+            for (int s = 0; s < St::STEPS; ++s) cv[s] = STREAM ? __builtin_nontemporal_load(c_at(0, s)) : *c_at(0, s);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            stage(i);
+            wave_lds_fence();
+            // all staged rows are fetched first, then stored
+            floatx4 v[St::STEPS];
+#pragma unroll
+            for (int s = 0; s < St::STEPS; ++s)
+                v[s] = *reinterpret_cast<const floatx4*>(region + (s * St::RPI + orow) * St::RS + ochunk * 16);
+#pragma unroll
+            for (int s = 0; s < St::STEPS; ++s) asm volatile("" : "+v"(v[s]));
             if (ACCUM) {
 #pragma unroll
-                for (int s = 0; s < St::STEPS; ++s) cv[s] = STREAM ? __builtin_nontemporal_load(c_at(0, s)) : *c_at(0, s);
+                for (int s = 0; s < St::STEPS; ++s) v[s] += cv[s];
+                if (i < 3) {
+#pragma unroll
+                    for (int s = 0; s < St::STEPS; ++s)
+                        cv[s] = STREAM ? __builtin_nontemporal_load(c_at(i + 1, s)) : *c_at(i + 1, s);
+                }
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                stage(i);
-                wave_lds_fence();
-                // all staged rows are fetched first, then stored
-                floatx4 v[St::STEPS];
-#pragma unroll
-                for (int s = 0; s < St::STEPS; ++s)
-                    v[s] = *reinterpret_cast<const floatx4*>(region + (s * St::RPI + orow) * St::RS + ochunk * 16);
-#pragma unroll
-                for (int s = 0; s < St::STEPS; ++s) asm volatile("" : "+v"(v[s]));
-                if (ACCUM) {
-#pragma unroll
-                    for (int s = 0; s < St::STEPS; ++s) v[s] += cv[s];
-                    if (i < 3) {
-#pragma unroll
-                        for (int s = 0; s < St::STEPS; ++s)
-                            cv[s] = STREAM ? __builtin_nontemporal_load(c_at(i + 1, s)) : *c_at(i + 1, s);
-                    }
-                }
-#pragma unroll
-                for (int s = 0; s < St::STEPS; ++s) {
-                    if (STREAM) __builtin_nontemporal_store(v[s], c_at(i, s));
-                    else *c_at(i, s) = v[s];
-                }
-                wave_lds_fence();
+            for (int s = 0; s < St::STEPS; ++s) {
+                if (STREAM) __builtin_nontemporal_store(v[s], c_at(i, s));
+                else *c_at(i, s) = v[s];
             }
-        } else {
+            wave_lds_fence();
+        }
+    } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row0 = m0 + wm * 128 + i * 32 + orow;
-                stage(i);
-                wave_lds_fence();
+        for (int i = 0; i < 4; ++i) {
+            const int row0 = m0 + wm * 128 + i * 32 + orow;
+            stage(i);
+            wave_lds_fence();
 #pragma unroll
-                for (int s = 0; s < St::STEPS; ++s) {
-                    const int rr = s * St::RPI + orow;
-                    const int row = row0 + s * St::RPI;
-                    const floatx4 v = *reinterpret_cast<const floatx4*>(region + rr * St::RS + ochunk * 16);
-                    if (row < g.M) store4_f32<ACCUM>(g.C + (size_t)row * g.ldc, col, g.N, vec, v);
-                }
-                wave_lds_fence();
+            for (int s = 0; s < St::STEPS; ++s) {
+                const int rr = s * St::RPI + orow;
+                const int row = row0 + s * St::RPI;
+                const floatx4 v = *reinterpret_cast<const floatx4*>(region + rr * St::RS + ochunk * 16);
+                if (row < g.M) store4_f32<ACCUM>(g.C + (size_t)row * g.ldc, col, g.N, vec, v);
             }
+            wave_lds_fence();
         }
     }
 }
