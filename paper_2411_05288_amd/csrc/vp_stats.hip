@@ -208,17 +208,19 @@ __global__ __launch_bounds__(256) void dlogits_kernel(const T* Y, T* D,   // may
 }
 
 // Vector form: one thread per 16 bytes of a row (8 bf16 or 4 fp32); needs Vs % (16/sizeof(T)) == 0.
+// Workgroup (x, y): row x, chunks 256 y .. 256 y + 255 of it: no division per thread, and the row's
+// statistics and label are the same for the whole workgroup.
 template <typename T, bool PRECISE>
 __global__ __launch_bounds__(256) void dlogits_vec_kernel(const T* Y, T* D,   // may alias (in place)
                                                           const int64_t* __restrict__ labels, int64_t off,
                                                           const float* __restrict__ gmax, const float* __restrict__ gsum,
-                                                          float scale, int chunks_per_row, int64_t total_chunks,
-                                                          int Vs, int64_t ldy, int64_t ldd) {
+                                                          float scale, int chunks_per_row, int Vs, int64_t ldy,
+                                                          int64_t ldd) {
     constexpr int E = 16 / (int)sizeof(T);
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;   // chunk of D: chunks_per_row = ldd / E
-    if (c >= total_chunks) return;
-    const int i = (int)(c / chunks_per_row);
-    const int j0 = (int)(c - (int64_t)i * chunks_per_row) * E;
+    const int i = blockIdx.x;
+    const int c = blockIdx.y * 256 + threadIdx.x;      // chunk of the row of D: chunks_per_row = ldd / E
+    if (c >= chunks_per_row) return;
+    const int j0 = c * E;
     if (j0 >= Vs) {   // padding of the row: zero, because the dH product multiplies it by zero
         *reinterpret_cast<uint4*>(D + (int64_t)i * ldd + j0) = make_uint4(0u, 0u, 0u, 0u);
         return;
@@ -286,14 +288,14 @@ hipError_t launch_dlogits(const void* Y, int64_t ldy, void* D, int64_t ldd, int 
     ProfScope prof(K_DLOGITS_EW, st);
     const int E = is_bf16 ? 8 : 4;
     if (Vs % E == 0 && ldd % E == 0 && ldy % E == 0 && ((((uintptr_t)Y) | ((uintptr_t)D)) & 15u) == 0) {
-        const int64_t total = (int64_t)N * (ldd / E);
-        const unsigned blocks = (unsigned)ceil_div(total, 256);
+        const int cpr = (int)(ldd / E);
+        const dim3 grid((unsigned)N, (unsigned)ceil_div(cpr, 256));     // rows in x: no 65535 limit on them
         if (is_bf16) {
-            hipLaunchKernelGGL((dlogits_vec_kernel<u16, false>), dim3(blocks), dim3(256), 0, st, (const u16*)Y, (u16*)D,
-                               labels, off, gmax, gsum, scale, (int)(ldd / E), total, Vs, ldy, ldd);
+            hipLaunchKernelGGL((dlogits_vec_kernel<u16, false>), grid, dim3(256), 0, st, (const u16*)Y, (u16*)D, labels,
+                               off, gmax, gsum, scale, cpr, Vs, ldy, ldd);
         } else {
-            hipLaunchKernelGGL((dlogits_vec_kernel<float, true>), dim3(blocks), dim3(256), 0, st, (const float*)Y,
-                               (float*)D, labels, off, gmax, gsum, scale, (int)(ldd / E), total, Vs, ldy, ldd);
+            hipLaunchKernelGGL((dlogits_vec_kernel<float, true>), grid, dim3(256), 0, st, (const float*)Y, (float*)D,
+                               labels, off, gmax, gsum, scale, cpr, Vs, ldy, ldd);
         }
         return hipGetLastError();
     }
