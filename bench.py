@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 # WRITE_SIZE, hence the factors.  Counters cannot be read from inside this process.
 PMC_FETCH_FACTOR, PMC_WRITE_FACTOR = 2.0, 1.0
 PMC_KIB = {   # kernel -> (FETCH_SIZE, WRITE_SIZE); dH is the accumulating launch (7 of 8 shards; the first one writes)
-    "cfg2_llama": {"gemm_bf16_fwd_stats": (100848.4, 36883.0), "gemm_bf16_dH": (134355.8, 66816.0),
-                   "gemm_bf16_dW": (98480.8, 64000.0)},
+    "cfg2_llama": {"gemm_bf16_fwd_stats": (100811.7, 36882.1), "gemm_bf16_dH": (134515.7, 66816.0),
+                   "gemm_bf16_dW": (98481.1, 64000.0)},
     "cfg3_large_vocab": {"gemm_bf16_fwd_stats": (487549.3, 143429.7), "gemm_bf16_dH": (535098.9, 66816.0),
                          "gemm_bf16_dW": (398088.1, 256857.8)},
     "cfg4_very_large_vocab": {"gemm_bf16_fwd_stats": (1055409.1, 6375.3), "gemm_bf16_dlogits": (1077840.5, 131859.2),
