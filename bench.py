@@ -34,8 +34,8 @@ PMC_FETCH_FACTOR, PMC_WRITE_FACTOR = 2.0, 1.0
 PMC_KIB = {   # kernel -> (FETCH_SIZE, WRITE_SIZE); dH is the accumulating launch (7 of 8 shards; the first one writes)
     "cfg2_llama": {"gemm_bf16_fwd_stats": (100811.7, 36882.1), "gemm_bf16_dH": (134515.7, 66816.0),
                    "gemm_bf16_dW": (98481.1, 64000.0)},
-    "cfg3_large_vocab": {"gemm_bf16_fwd_stats": (487549.3, 143429.7), "gemm_bf16_dH": (535098.9, 66816.0),
-                         "gemm_bf16_dW": (398088.1, 256857.8)},
+    "cfg3_large_vocab": {"gemm_bf16_fwd_stats": (482860.5, 143630.4), "gemm_bf16_dH": (459801.5, 66816.0),
+                         "gemm_bf16_dW": (397501.3, 256959.8)},
     "cfg4_very_large_vocab": {"gemm_bf16_fwd_stats": (1055409.1, 6375.3), "gemm_bf16_dlogits": (1077840.5, 131859.2),
                               "gemm_bf16_dH": (837516.9, 132566.1), "gemm_bf16_dW": (884055.2, 513068.6)},
 }
