@@ -130,3 +130,16 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    # the product path has no CPU fallback: without libvp.so every entry point raises
+    import paper_2411_05288_amd.binding as B
+    monkeypatch.setattr(B, "_LIB", None)
+    monkeypatch.setattr(B, "lib_path", lambda: "/nonexistent/libvp.so")
+    with pytest.raises(B.VPError):
+        B.load_library()
+    with pytest.raises(B.VPError):
+        B.vp_version()
+    with pytest.raises(B.VPError):
+        B.vp_workspace_bytes(B.VP_CALL_OUTPUT_FWD, 8, 8, 8, B.VP_BF16, 0)
