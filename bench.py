@@ -219,6 +219,69 @@ def mfma_sustained(vp, cfg):
     return res
 
 
+def gemm_timeline(vp, cfg, reps=3):
+    """Itemised time budget of the fast GEMM launches of the last shard's passes S and T, from the phase stamps the
+    kernel writes when its timeline is switched on (vp_profile_gemm_trace): per workgroup and output tile, the
+    100 MHz counter and the shader clock at tile start, first operands landed, main loop done, epilogue done.
+    All figures in microseconds per launch, averaged over workgroups (and over `reps` launches)."""
+    import torch
+    pl = make_output_plan(vp, cfg, seeded_numpy=False)
+    for _ in range(2):
+        pl.step()
+    torch.cuda.synchronize()
+    buf = torch.zeros(8 + 256 * 64 * 8, dtype=torch.int64, device="cuda")
+    runs = ["gemm_bf16_fwd_stats", "gemm_bf16_dH", "gemm_bf16_dW"]
+    if not cfg.save_logits:
+        runs.insert(1, "gemm_bf16_dlogits")
+    out = {}
+    for name in runs:
+        acc = []
+        for _ in range(reps):
+            # whole steps back to back, so that the traced launch (the last one of this kernel: every launch
+            # overwrites the records) runs in the clock and cache state of the timed benchmark
+            buf.zero_()
+            vp.vp_profile_gemm_trace(buf, name)
+            pl.step()
+            pl.step()
+            torch.cuda.synchronize()
+            vp.vp_profile_gemm_trace(None)
+            w = buf.cpu().numpy()
+            grid, tiles, cap = int(w[0]), int(w[1]), int(w[2])
+            rec = w[8:8 + grid * cap * 8].reshape(grid, cap, 4, 2).astype(np.float64)
+            valid = rec[:, :, 3, 0] > 0                      # tiles this workgroup really had
+            t = rec[:, :, :, 0] * 0.01                        # 100 MHz counter -> microseconds
+            clk = rec[:, :, :, 1]
+            t0 = t[:, 0, 0].min()
+            end = np.where(valid, t[:, :, 3], 0).max(axis=1)  # last stamp of every workgroup
+            span = end.max() - t0
+            pro = np.where(valid, t[:, :, 1] - t[:, :, 0], 0).sum(axis=1)
+            main = np.where(valid, t[:, :, 2] - t[:, :, 1], 0).sum(axis=1)
+            epi = np.where(valid, t[:, :, 3] - t[:, :, 2], 0).sum(axis=1)
+            start_skew = (t[:, 0, 0] - t0)
+            main_clk = np.where(valid, clk[:, :, 2] - clk[:, :, 1], 0).sum() / max(main.sum(), 1e-9) / 1e3   # GHz
+            acc.append({"span_us": span, "prologue_us": pro.mean(), "main_loop_us": main.mean(),
+                        "epilogue_us": epi.mean(), "launch_skew_us": start_skew.mean(),
+                        "idle_at_end_us": (end.max() - end).mean(),
+                        "tiles": tiles, "workgroups": grid, "tiles_per_workgroup_max": cap,
+                        "main_loop_clock_GHz": main_clk,
+                        "epilogue_us_per_tile": np.where(valid, t[:, :, 3] - t[:, :, 2], 0).sum() / valid.sum(),
+                        "main_loop_us_per_tile": np.where(valid, t[:, :, 2] - t[:, :, 1], 0).sum() / valid.sum()})
+            # workgroups are dealt to the 8 XCDs round-robin: busy time (all phases) per XCD, and its spread
+            busy = pro + main + epi
+            acc[-1]["busy_us_min"] = busy.min()
+            acc[-1]["busy_us_max"] = busy.max()
+            for x in range(8):
+                acc[-1]["busy_us_xcd%d" % x] = busy[x::8].mean()
+        out[name] = {k: float(np.mean([a[k] for a in acc])) for k in acc[0]}
+        flops = 2.0 * cfg.N * cfg.h * cfg.Vs
+        out[name]["main_loop_tflops"] = flops / (out[name]["main_loop_us"] * 1e-6) / 1e12 * (
+            out[name]["tiles"] / (out[name]["workgroups"] * out[name]["tiles_per_workgroup_max"]))
+        out[name]["span_tflops"] = flops / (out[name]["span_us"] * 1e-6) / 1e12
+    del pl
+    torch.cuda.empty_cache()
+    return out
+
+
 def bench_barrier_overlap(vp, cfg, steps):
     """The barrier's on-device work (vp_combine_stats) on a side stream of default priority while the
     next pass S (a stand-in for the transformer work the paper overlaps its barriers with) runs on the
@@ -273,6 +336,9 @@ def main():
                     help="also run a plain elementwise copy of 256 MiB (read 256 MiB, write 256 MiB) five times, so "
                          "that a counter run of this command carries a kernel of known HBM traffic")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="0 = all token rows of the workload")
+    ap.add_argument("--timeline", action="store_true",
+                    help="only print the itemised per-launch time budget (prologue / main loop / epilogue / idle) of "
+                         "the GEMM kernels of --config, from the kernel's own phase stamps")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the p shards of a configuration run in sequence "
@@ -288,6 +354,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     cfg = si.CONFIGS[args.config]
+    if args.timeline:
+        print(json.dumps({"timeline": gemm_timeline(vp, cfg), "config": cfg.name}))
+        return
     if isinstance(cfg, si.EmbedConfig):
         # profiling aid: only the input-layer configuration, reported in GB/s of algorithmic bytes
         emb = bench_embedding(vp, cfg, args.steps, args.warmup)

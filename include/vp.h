@@ -61,8 +61,8 @@ typedef enum {
 enum {
     VP_SAVE_LOGITS = 1u, /* fwd: store the logits; bwd: the stored logits are supplied */
     VP_SKIP_DH = 2u,     /* vp_output_bwd only: pass T of Algorithm 2, dW_shard alone (dH_accum may be NULL) */
-    VP_DH_OVERWRITE = 4u /* vp_output_bwd only: dH_accum = D W_shard instead of +=: the first term of the reduce C2,
-                            which saves zero-filling dH_accum and reading the zeros back */
+    VP_DH_OVERWRITE = 4u /* vp_output_bwd, vp_output_dx_alg2: dH_accum = (this shard's term) instead of +=: the first
+                            term of the reduce C2, which saves zero-filling dH_accum and reading the zeros back */
 };
 
 /* Library version (major*10000 + minor*100 + patch). Host-only, no device work. */
@@ -125,6 +125,15 @@ vp_status vp_combine_stats(const float* local_max, const float* local_sumexp, co
  * With VP_SKIP_DH only dW_shard is formed (pass T of Algorithm 2, section 4.4, where the input
  * gradient has already left through vp_output_dx_alg2); dH_accum is then ignored and may be NULL.
  */
+/*
+ * Row stride (elements) of the D matrix that vp_output_bwd leaves at the start of its workspace:
+ * on return (once the stream has run the call) the workspace begins with D as [N, stride] in type
+ * dt, columns Vs .. stride-1 zero.  With VP_BF16 rows are padded to 128 bytes, with VP_F32 the
+ * matrix is dense.  This is how tests compare D itself with the definition; the rest of the
+ * workspace stays undefined.  Host-only; returns -1 for invalid arguments.
+ */
+int64_t vp_dlogits_row_stride(int64_t Vs, vp_dtype dt);
+
 vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* labels,
                         int64_t N, int64_t h, int64_t Vs, int64_t shard_offset,
                         vp_dtype dt, uint32_t flags,
@@ -157,13 +166,15 @@ vp_status vp_output_fwd_alg2(const void* H, const void* W_shard, const int64_t* 
  *     c_i = local_sumexp[i] * exp(local_max[i] - global_max[i]) / global_sumexp[i]
  * (c_i = 0 for a shard whose local_max is -inf).  Calling the p shards in ascending order is
  * the deterministic reduce.  Pass T of Algorithm 2 is vp_output_bwd with VP_SKIP_DH.
+ * flags: 0, or VP_DH_OVERWRITE for the first term of the reduce (dH_accum = ... instead of +=, so the
+ * caller need not zero-fill it).
  *   A [N,h] : in, fp32.  B [N,h] : in, type dt.  local_* / global_* [N] : in, fp32.
- *   dH_accum [N,h] : in/out, fp32.
+ *   dH_accum [N,h] : in/out (out only with VP_DH_OVERWRITE), fp32.
  */
 vp_status vp_output_dx_alg2(const float* A, const void* B,
                             const float* local_max, const float* local_sumexp,
                             const float* global_max, const float* global_sumexp,
-                            int64_t N, int64_t h, vp_dtype dt, float grad_scale,
+                            int64_t N, int64_t h, vp_dtype dt, uint32_t flags, float grad_scale,
                             float* dH_accum, void* stream);
 
 /*
@@ -203,6 +214,27 @@ vp_status vp_profile_enable(int on);
 vp_status vp_profile_read(double* ms_total, int64_t* launches, int n);
 
 /*
+ * Test switch, not part of the method: while on, every bf16 product goes through the generic GEMM
+ * kernel (element-wise predicated loads) instead of the fast one, so that tests can compare the two on
+ * shapes the fast kernel would normally take.  Process-wide; off by default.
+ */
+vp_status vp_profile_force_generic_gemm(int on);
+
+/*
+ * Measurement aid, not part of the method: a timeline of the fast bf16 GEMM kernel.  While `buffer`
+ * (device memory, 8-byte aligned, owned by the caller) is set, every launch of that kernel whose records
+ * fit writes, per workgroup and output tile, four phase stamps - tile start, operands of the first k
+ * tile landed, main loop done, epilogue done (stores issued) - each as {100 MHz counter, shader clock}:
+ *     word 0: workgroups; word 1: output tiles; word 2: tiles per workgroup T;
+ *     words 8 + ((w * T + t) * 8) .. +7 : stamps of tile t of workgroup w.
+ * A launch overwrites the previous one's records.  kernel_id >= 0 (an index of vp_profile_kernel_name)
+ * restricts the trace to the launches timed under that name, < 0 takes every fast GEMM launch.
+ * buffer = NULL switches it off (the default).  Process-wide; launches that race with a change of the
+ * buffer see either setting.
+ */
+vp_status vp_profile_gemm_trace(void* buffer, size_t bytes, int kernel_id);
+
+/*
  * Measurement aid, not part of the method: `blocks` workgroups of 4 wavefronts each run `iters` x 16
  * back-to-back v_mfma_f32_32x32x16_bf16 on register operands, with no memory traffic inside the loop
  * (blocks * 4 * iters * 16 * 32768 flops in total).  The matrix cores are power limited and the rate they
@@ -211,6 +243,24 @@ vp_status vp_profile_read(double* ms_total, int64_t* launches, int n);
  *   out      : out, device, blocks * 256 floats (keeps the work observable; contents are meaningless).
  */
 vp_status vp_profile_mfma_loop(const void* operands, float* out, int32_t iters, int32_t blocks, void* stream);
+
+/*
+ * The same measurement for other instruction shapes and issue orders, so that the ceiling is an
+ * envelope and not one point.  Every wavefront owns a 128 x 128 block of accumulators:
+ *   variant 0  v_mfma_f32_32x32x16_bf16, 4 x 4 tiles column by column (= vp_profile_mfma_loop)
+ *           1  the same in a snake (one operand changes between consecutive instructions)
+ *           2  two k sub-steps chained back to back on each accumulator
+ *           3  four k sub-steps chained back to back on each accumulator
+ *           4  v_mfma_f32_16x16x32_bf16, 8 x 8 tiles column by column
+ *           5  the same in a snake
+ * vp_profile_mfma_variant_flops(variant) is the flop count of one wavefront in one iteration
+ * (total = blocks * 4 * iters * that); vp_profile_mfma_variant_count() the number of variants.
+ *   operands : in, device, 32 * 256 * 16 bytes of bf16.   out : out, device, blocks * 256 floats.
+ */
+vp_status vp_profile_mfma_variant(const void* operands, float* out, int32_t iters, int32_t blocks, int32_t variant,
+                                  void* stream);
+int vp_profile_mfma_variant_count(void);
+double vp_profile_mfma_variant_flops(int32_t variant);
 
 #ifdef __cplusplus
 }

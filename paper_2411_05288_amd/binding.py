@@ -56,6 +56,8 @@ def load_library() -> ctypes.CDLL:
     lib.vp_status_string.argtypes = [c.c_int]
     lib.vp_workspace_bytes.restype = sz
     lib.vp_workspace_bytes.argtypes = [c.c_int, i64, i64, i64, c.c_int, u32]
+    lib.vp_dlogits_row_stride.restype = i64
+    lib.vp_dlogits_row_stride.argtypes = [i64, c.c_int]
     lib.vp_output_fwd.restype = c.c_int
     lib.vp_output_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i64, c.c_int, u32, vp, vp, vp, vp, vp, sz, vp]
     lib.vp_combine_stats.restype = c.c_int
@@ -65,13 +67,23 @@ def load_library() -> ctypes.CDLL:
     lib.vp_output_fwd_alg2.restype = c.c_int
     lib.vp_output_fwd_alg2.argtypes = [vp, vp, vp, i64, i64, i64, i64, c.c_int, u32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.vp_output_dx_alg2.restype = c.c_int
-    lib.vp_output_dx_alg2.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, c.c_int, fl, vp, vp]
+    lib.vp_output_dx_alg2.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, c.c_int, u32, fl, vp, vp]
     lib.vp_embed_fwd.restype = c.c_int
     lib.vp_embed_fwd.argtypes = [vp, vp, i64, i64, i64, i64, c.c_int, vp, vp]
     lib.vp_embed_bwd.restype = c.c_int
     lib.vp_embed_bwd.argtypes = [vp, vp, i64, i64, i64, i64, c.c_int, vp, vp, sz, vp]
     lib.vp_profile_mfma_loop.restype = c.c_int
     lib.vp_profile_mfma_loop.argtypes = [vp, vp, i32, i32, vp]
+    lib.vp_profile_mfma_variant.restype = c.c_int
+    lib.vp_profile_mfma_variant.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.vp_profile_mfma_variant_count.restype = c.c_int
+    lib.vp_profile_mfma_variant_count.argtypes = []
+    lib.vp_profile_mfma_variant_flops.restype = c.c_double
+    lib.vp_profile_mfma_variant_flops.argtypes = [i32]
+    lib.vp_profile_force_generic_gemm.restype = c.c_int
+    lib.vp_profile_force_generic_gemm.argtypes = [c.c_int]
+    lib.vp_profile_gemm_trace.restype = c.c_int
+    lib.vp_profile_gemm_trace.argtypes = [vp, sz, c.c_int]
     lib.vp_profile_kernel_count.restype = c.c_int
     lib.vp_profile_kernel_count.argtypes = []
     lib.vp_profile_kernel_name.restype = c.c_char_p
@@ -131,6 +143,13 @@ def vp_workspace_bytes(which: int, N: int, h: int, Vs: int, dt: int, flags: int 
     n = load_library().vp_workspace_bytes(which, N, h, Vs, dt, flags)
     if n == ctypes.c_size_t(-1).value:
         raise VPError("vp_workspace_bytes: invalid arguments")
+    return n
+
+
+def vp_dlogits_row_stride(Vs: int, dt: int) -> int:
+    n = load_library().vp_dlogits_row_stride(Vs, dt)
+    if n < 0:
+        raise VPError("vp_dlogits_row_stride: invalid arguments")
     return n
 
 
@@ -220,16 +239,17 @@ def vp_output_fwd_alg2(H, W_shard, labels, shard_offset: int, local_max, local_s
 
 
 def vp_output_dx_alg2(A, B, local_max, local_sumexp, global_max, global_sumexp, grad_scale: float, dH_accum,
-                      stream=None) -> None:
-    """dH_accum += (A * sum' e^{m'-m} / sum - B) * grad_scale: this shard's term of Algorithm 2's input gradient."""
+                      stream=None, dh_overwrite: bool = False) -> None:
+    """dH_accum += (A * sum' e^{m'-m} / sum - B) * grad_scale: this shard's term of Algorithm 2's input gradient
+    (dh_overwrite=True, flag VP_DH_OVERWRITE: = instead of +=, the first term of the reduce)."""
     N, h = A.shape
     f = (torch.float32,)
     dt = _dtype_code(B)
     st = load_library().vp_output_dx_alg2(
         _ptr(A, "A", f, (N, h)), _ptr(B, "B", None, (N, h)), _ptr(local_max, "local_max", f, (N,)),
         _ptr(local_sumexp, "local_sumexp", f, (N,)), _ptr(global_max, "global_max", f, (N,)),
-        _ptr(global_sumexp, "global_sumexp", f, (N,)), N, h, dt, float(grad_scale),
-        _ptr(dH_accum, "dH_accum", f, (N, h)), _stream(stream))
+        _ptr(global_sumexp, "global_sumexp", f, (N,)), N, h, dt, VP_DH_OVERWRITE if dh_overwrite else 0,
+        float(grad_scale), _ptr(dH_accum, "dH_accum", f, (N, h)), _stream(stream))
     _check(st, "vp_output_dx_alg2")
 
 
@@ -261,6 +281,44 @@ def vp_profile_mfma_loop(operands, out, iters: int, blocks: int, stream=None) ->
     st = load_library().vp_profile_mfma_loop(_ptr(operands, "operands", _BF16_LIKE), _ptr(out, "out", (torch.float32,)),
                                              iters, blocks, _stream(stream))
     _check(st, "vp_profile_mfma_loop")
+
+
+def vp_profile_mfma_variant(operands, out, iters: int, blocks: int, variant: int, stream=None) -> float:
+    """Measurement aid: the MFMA loop in another instruction shape / issue order (see include/vp.h).
+    Returns the flop count of the launch."""
+    lib = load_library()
+    if operands.numel() * operands.element_size() < 32 * 256 * 16 or out.numel() < blocks * 256:
+        raise VPError("vp_profile_mfma_variant: buffers too small")
+    st = lib.vp_profile_mfma_variant(_ptr(operands, "operands", _BF16_LIKE), _ptr(out, "out", (torch.float32,)),
+                                     iters, blocks, variant, _stream(stream))
+    _check(st, "vp_profile_mfma_variant")
+    return lib.vp_profile_mfma_variant_flops(variant) * blocks * 4 * iters
+
+
+def vp_profile_mfma_variant_count() -> int:
+    return load_library().vp_profile_mfma_variant_count()
+
+
+def vp_profile_force_generic_gemm(on: bool) -> None:
+    """Test switch: route every bf16 product through the generic GEMM kernel."""
+    _check(load_library().vp_profile_force_generic_gemm(1 if on else 0), "vp_profile_force_generic_gemm")
+
+
+def vp_profile_gemm_trace(buffer, kernel: Optional[str] = None) -> None:
+    """Measurement aid: phase stamps of the fast GEMM kernel into `buffer` (a GPU tensor of int64; None = off),
+    optionally only for launches timed under the kernel name `kernel` (see vp_profile_read)."""
+    lib = load_library()
+    if buffer is None:
+        _check(lib.vp_profile_gemm_trace(None, 0, -1), "vp_profile_gemm_trace")
+        return
+    kid = -1
+    if kernel is not None:
+        names = [lib.vp_profile_kernel_name(i).decode() for i in range(lib.vp_profile_kernel_count())]
+        if kernel not in names:
+            raise VPError("unknown kernel name %r" % kernel)
+        kid = names.index(kernel)
+    _check(lib.vp_profile_gemm_trace(_ptr(buffer, "buffer", (torch.int64,)), buffer.numel() * 8, kid),
+           "vp_profile_gemm_trace")
 
 
 def vp_profile_enable(on: bool) -> None:

@@ -151,6 +151,11 @@ vp_status vp_combine_stats(const float* local_max, const float* local_sumexp, co
                               loss_per_row, loss_mean, (hipStream_t)stream));
 }
 
+int64_t vp_dlogits_row_stride(int64_t Vs, vp_dtype dt) {
+    if (Vs < 1 || !dtype_ok(dt)) return -1;
+    return dt == VP_BF16 ? d_row_stride(Vs) : Vs;
+}
+
 vp_status vp_output_bwd(const void* H, const void* W_shard, const int64_t* labels, int64_t N, int64_t h, int64_t Vs,
                         int64_t shard_offset, vp_dtype dt, uint32_t flags, const float* global_max,
                         const float* global_sumexp, const void* logits_saved, float grad_scale, float* dH_accum,
@@ -325,14 +330,14 @@ vp_status vp_output_fwd_alg2(const void* H, const void* W_shard, const int64_t* 
 
 vp_status vp_output_dx_alg2(const float* A, const void* B, const float* local_max, const float* local_sumexp,
                             const float* global_max, const float* global_sumexp, int64_t N, int64_t h, vp_dtype dt,
-                            float grad_scale, float* dH_accum, void* stream) {
+                            uint32_t flags, float grad_scale, float* dH_accum, void* stream) {
     if (!A || !B || !local_max || !local_sumexp || !global_max || !global_sumexp || !dH_accum)
         return VP_ERR_INVALID_ARG;
-    if (N < 1 || h < 1 || !dtype_ok(dt)) return VP_ERR_INVALID_ARG;
+    if (N < 1 || h < 1 || !dtype_ok(dt) || (flags & ~(uint32_t)VP_DH_OVERWRITE)) return VP_ERR_INVALID_ARG;
     if (!aligned16(A) || !aligned16(B) || !aligned16(dH_accum)) return VP_ERR_INVALID_ARG;
     if (N >= MAX_ELEMS || h >= MAX_ELEMS || N * h >= MAX_ELEMS) return VP_ERR_UNSUPPORTED;
     return dev(launch_dx_alg2(A, B, dt == VP_BF16 ? 1 : 0, local_max, local_sumexp, global_max, global_sumexp, (int)N,
-                              (int)h, grad_scale, dH_accum, (hipStream_t)stream));
+                              (int)h, grad_scale, (flags & VP_DH_OVERWRITE) != 0, dH_accum, (hipStream_t)stream));
 }
 
 vp_status vp_embed_fwd(const void* table_shard, const int64_t* ids, int64_t N, int64_t h, int64_t Vs,

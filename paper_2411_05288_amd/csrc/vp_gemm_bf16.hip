@@ -13,7 +13,7 @@
 // MFMA 32x32x16 operand layout (wave64): lane l supplies row (l % 32) of its operand and the
 // 8 consecutive k values starting at 8 * (l / 32).  The accumulator layout and the epilogues
 // are shared with the fast kernel.
-#include <stdlib.h>
+#include <atomic>
 
 #include "vp_gemm_bf16_common.h"
 
@@ -171,6 +171,10 @@ static hipError_t launch_t(const GemmBf16Params& p, hipStream_t st) {
     return hipGetLastError();
 }
 
+// Test switch: route every product through the generic kernel.
+static std::atomic<bool> g_force_generic{false};
+void gemm_bf16_force_generic(bool on) { g_force_generic.store(on, std::memory_order_relaxed); }
+
 hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st) {
     if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
     // the epilogue addresses the 256 rows of an output tile with 32-bit byte offsets
@@ -182,8 +186,11 @@ hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st) {
                   : p.epi == Epi::DLogits  ? K_GEMM_DLOGITS
                   : p.epi == Epi::AccumF32 ? K_GEMM_DH : K_GEMM_DW;
     ProfScope prof(kid, st);
-    const char* force = getenv("VP_FORCE_GENERIC_GEMM");
-    if (!(force && force[0] == '1') && gemm_bf16_fast_ok(p)) return launch_gemm_bf16_fast(p, st);
+    if (!g_force_generic.load(std::memory_order_relaxed) && gemm_bf16_fast_ok(p)) {
+        GemmBf16Params q = p;
+        q.kernel_id = kid;
+        return launch_gemm_bf16_fast(q, st);
+    }
     // only the operand-layout / epilogue combinations the output layer uses are instantiated
     if (p.a_kcontig && p.b_kcontig && p.epi == Epi::FwdStats) return launch_t<true, true, Epi::FwdStats>(p, st);
     if (p.a_kcontig && p.b_kcontig && p.epi == Epi::DLogits) return launch_t<true, true, Epi::DLogits>(p, st);

@@ -29,6 +29,8 @@
 //       points at k-row kb + s/4, rows nb + 4*(s%4)..+3, and lane i receives rows nb + i for
 //       the four k-rows kb..kb+3.  f makes the 4 k-rows of a group, and the 8 of two groups,
 //       fall into different banks.
+#include <atomic>
+
 #include "vp_gemm_bf16_common.h"
 
 namespace vp {
@@ -39,8 +41,16 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 constexpr int TILE_BYTES = 32768;             // one operand tile
 constexpr int STAGE_BYTES_F = 2 * TILE_BYTES; // A tile then B tile
 
+// Two separate arrays: every LDS address of the main loop is then "array base + offset below 64 KB",
+// which fits the 16-bit offset field of the LDS instructions (one array of 128 KB costs address
+// arithmetic in the main loop: measured 25 % slower).  Nothing relies on how the two are placed
+// relative to each other: the epilogue's exchange area and the staging blocks of wavefronts 0 and 1
+// lie in stage 0, the staging blocks of wavefronts 2 and 3 in stage 1.
 __shared__ __attribute__((aligned(1024))) char g_stage0[STAGE_BYTES_F];
 __shared__ __attribute__((aligned(1024))) char g_stage1[STAGE_BYTES_F];
+static_assert(EPI_XCHG_BYTES + 2 * StageF32<128>::BYTES <= STAGE_BYTES_F, "epilogue staging exceeds LDS stage 0");
+static_assert(2 * StageF32<128>::BYTES <= STAGE_BYTES_F, "epilogue staging exceeds LDS stage 1");
+static_assert(StageBf16<128>::BYTES <= StageF32<128>::BYTES, "bf16 staging block larger than the fp32 one");
 
 __device__ __forceinline__ int seg_swizzle(int k_low2) { return k_low2 ^ ((k_low2 & 1) << 2); }
 
@@ -151,7 +161,23 @@ __device__ __forceinline__ void mfma_step(floatx16 (&acc)[4][4], const bf16x8 (&
         }
 }
 
-template <bool A_KC, bool B_KC, Epi EPI, bool STREAM>
+// Phase stamps of the optional timeline (measurement aid): per workgroup and tile, the constant
+// 100 MHz counter and the shader clock at tile start, after the prologue's first barrier, at the
+// end of the main loop and at the end of the epilogue (stores issued, not necessarily landed).
+constexpr int TRACE_STAMPS = 8;          // 4 phases x {real time, shader clock}
+constexpr int TRACE_HEADER = 8;          // words before the first record
+template <bool TRACE>
+__device__ __forceinline__ void trace_stamp(const GemmBf16Params& g, int tile_idx, int phase) {
+    if constexpr (TRACE) {
+        if (threadIdx.x == 0 && tile_idx < g.trace_cap) {
+            unsigned long long* r = g.trace + TRACE_HEADER + ((size_t)blockIdx.x * g.trace_cap + tile_idx) * TRACE_STAMPS;
+            r[2 * phase] = wall_clock64();
+            r[2 * phase + 1] = clock64();
+        }
+    }
+}
+
+template <bool A_KC, bool B_KC, Epi EPI, bool STREAM, bool TRACE>
 __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -175,7 +201,12 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     // gridDim.x.  The stores of a tile's epilogue are fire-and-forget, so they drain while the
     // next tile's operands are already streaming in.  Virtual id v keeps the XCD-aware tile
     // order: v % 8 is the XCD of this workgroup for every tile it processes.
-    for (int v = blockIdx.x; v < total_tiles; v += gridDim.x) {
+    if (TRACE && blockIdx.x == 0 && tid == 0) {
+        g.trace[0] = gridDim.x; g.trace[1] = (unsigned long long)total_tiles; g.trace[2] = (unsigned long long)g.trace_cap;
+    }
+    int tile_idx = 0;
+    for (int v = blockIdx.x; v < total_tiles; v += gridDim.x, ++tile_idx) {
+    trace_stamp<TRACE>(g, tile_idx, 0);
     int tile_m, tile_n;
     tile_of_block(v, gridDim.x, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -206,6 +237,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     // prologue: tile 0 -> stage 0 completely, then the first half of tile 1 -> stage 1
     issue_loads<0, 16>(g, a_bytes, b_bytes, 0u, 0u, avoff, bvoff, g_stage0, wave);
     __syncthreads();
+    trace_stamp<TRACE>(g, tile_idx, 1);
     issue_loads<0, 8>(g, a_bytes, b_bytes, a_kstep, b_kstep, avoff, bvoff, g_stage1, wave);
     bf16x8 af0[4], bf0[4], af1[4], bf1[4];
     read_frags<A_KC, B_KC>(af0, bf0, g_stage0, abase, bbase, 0);
@@ -283,38 +315,68 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
 #undef VP_SCHED_DSRD
 #undef VP_SCHED_VMEM
     __syncthreads();   // every wavefront is done with the stages before the epilogue reuses them
+    trace_stamp<TRACE>(g, tile_idx, 2);
 
     // keep the epilogue's address arithmetic from being hoisted above the main loop, where it
     // would occupy registers (and spill) for the whole kernel
     asm volatile("" : "+s"(tile_m), "+s"(tile_n));
     gemm_epilogue<EPI, 4, 2, STREAM>(acc, g, tile_m, tile_n, g_stage0,
-                                     g_stage0 + EPI_XCHG_BYTES + wave * StageF32<128>::BYTES);
+                                     wave < 2 ? g_stage0 + EPI_XCHG_BYTES + wave * StageF32<128>::BYTES
+                                              : g_stage1 + (wave - 2) * StageF32<128>::BYTES);
     __syncthreads();   // the epilogue's LDS exchange is over before the next tile streams in
+    trace_stamp<TRACE>(g, tile_idx, 3);
     }   // persistent tile loop
 }
 
 // Compute units of the current device (one persistent workgroup each); queried once per device.
 static int compute_unit_count() {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);   // every thread computes the same value
     }
-    return cached[dev];
+    return n;
+}
+
+// Timeline buffer of the measurement aid (device memory owned by the caller of vp_profile_gemm_trace).
+static std::atomic<unsigned long long*> g_trace_buf{nullptr};
+static std::atomic<size_t> g_trace_words{0};
+static std::atomic<int> g_trace_kernel{-1};
+
+void gemm_bf16_set_trace(void* buf, size_t bytes, int kernel_id) {
+    g_trace_words.store(buf ? bytes / sizeof(unsigned long long) : 0);
+    g_trace_kernel.store(kernel_id);
+    g_trace_buf.store((unsigned long long*)buf);
 }
 
 template <bool A_KC, bool B_KC, Epi EPI>
-static hipError_t launch_fast_t(const GemmBf16Params& p, hipStream_t st) {
+static hipError_t launch_fast_t(const GemmBf16Params& p0, hipStream_t st) {
+    GemmBf16Params p = p0;
     const int tiles = (int)(ceil_div(p.M, BM) * ceil_div(p.N, BN));
     const int cus = compute_unit_count();
+    const int grid = tiles > cus ? cus : tiles;
+    unsigned long long* tb = g_trace_buf.load();
+    const int want = g_trace_kernel.load();
+    if (tb && (want < 0 || want == p.kernel_id)) {   // measurement aid: the instrumented instantiation, if the buffer holds this launch's records
+        const int per_wg = (int)ceil_div(tiles, grid);
+        if ((size_t)TRACE_HEADER + (size_t)grid * per_wg * TRACE_STAMPS <= g_trace_words.load()) {
+            p.trace = tb;
+            p.trace_cap = per_wg;
+            if (tiles > cus)
+                hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI, true, true>), dim3(grid), dim3(NT), 0, st, p);
+            else
+                hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI, false, true>), dim3(grid), dim3(NT), 0, st, p);
+            return hipGetLastError();
+        }
+    }
     // more tiles than workgroups: outputs are streamed past the L2 (see gemm_epilogue)
     if (tiles > cus)
-        hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI, true>), dim3(cus), dim3(NT), 0, st, p);
+        hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI, true, false>), dim3(grid), dim3(NT), 0, st, p);
     else
-        hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI, false>), dim3(tiles), dim3(NT), 0, st, p);
+        hipLaunchKernelGGL((gemm_bf16_fast_kernel<A_KC, B_KC, EPI, false, false>), dim3(grid), dim3(NT), 0, st, p);
     return hipGetLastError();
 }
 

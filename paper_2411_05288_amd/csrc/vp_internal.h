@@ -70,12 +70,18 @@ struct GemmBf16Params {
     const float* gmax;   // DLogits: [M]
     const float* gsum;   // DLogits: [M]
     float scale;         // DLogits
-    int kernel_id;       // timing slot; 0 = chosen from the epilogue
+    int kernel_id;       // timing slot; 0 = chosen from the epilogue (resolved by launch_gemm_bf16)
+    unsigned long long* trace;   // measurement aid: phase stamps per workgroup and tile (nullptr: none)
+    int trace_cap;               // tiles per workgroup the trace buffer holds
 };
 
-// Dispatches to the fast kernel when its preconditions hold (and the environment variable
-// VP_FORCE_GENERIC_GEMM is not set to 1), else to the generic kernel.
+// Dispatches to the fast kernel when its preconditions hold (and the generic kernel has not been
+// forced through vp_profile_force_generic_gemm), else to the generic kernel.
 hipError_t launch_gemm_bf16(const GemmBf16Params& p, hipStream_t st);
+void gemm_bf16_force_generic(bool on);
+// Measurement aid: device buffer into which the fast kernel's next launches write their phase stamps
+// (nullptr: off); kernel_id >= 0 restricts it to the launches timed under that kernel id.
+void gemm_bf16_set_trace(void* buf, size_t bytes, int kernel_id);
 bool gemm_bf16_fast_ok(const GemmBf16Params& p);
 hipError_t launch_gemm_bf16_fast(const GemmBf16Params& p, hipStream_t st);
 
@@ -108,8 +114,9 @@ hipError_t launch_dlogits(const void* Y, int64_t ldy, void* D, int64_t ldd, int 
                           hipStream_t st);
 
 // dH += (A * c - B) * scale with c_i = lsum_i exp(lmax_i - gmax_i) / gsum_i  (Algorithm 2)
+// (overwrite: dH = ... instead of +=)
 hipError_t launch_dx_alg2(const float* A, const void* B, int b_is_bf16, const float* lmax, const float* lsum,
-                          const float* gmax, const float* gsum, int N, int h, float scale, float* dH,
+                          const float* gmax, const float* gsum, int N, int h, float scale, bool overwrite, float* dH,
                           hipStream_t st);
 
 // Zeroes the padding columns Vs .. ldd-1 of the bf16 matrix D [N, ldd].

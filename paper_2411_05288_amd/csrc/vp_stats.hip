@@ -320,8 +320,9 @@ hipError_t launch_dlogits(const void* Y, int64_t ldy, void* D, int64_t ldd, int 
     return hipSuccess;
 }
 
-// Input gradient of Algorithm 2 (section 4.4): dH += (A c - B) scale, one thread per 4 columns.
-template <typename TB>
+// Input gradient of Algorithm 2 (section 4.4): dH += (A c - B) scale (OVERWRITE: dH = ...), one thread per
+// 4 columns.
+template <typename TB, bool OVERWRITE>
 __global__ __launch_bounds__(256) void dx_alg2_kernel(const float* __restrict__ A, const TB* __restrict__ Bm,
                                                       const float* __restrict__ lmax, const float* __restrict__ lsum,
                                                       const float* __restrict__ gmax, const float* __restrict__ gsum,
@@ -344,7 +345,7 @@ __global__ __launch_bounds__(256) void dx_alg2_kernel(const float* __restrict__ 
             const float4 w = *reinterpret_cast<const float4*>(Bm + e0);
             b[0] = w.x; b[1] = w.y; b[2] = w.z; b[3] = w.w;
         }
-        float4 d = *reinterpret_cast<const float4*>(dH + e0);
+        float4 d = OVERWRITE ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4*>(dH + e0);
         d.x += (a.x * c - b[0]) * scale;
         d.y += (a.y * c - b[1]) * scale;
         d.z += (a.z * c - b[2]) * scale;
@@ -355,23 +356,33 @@ __global__ __launch_bounds__(256) void dx_alg2_kernel(const float* __restrict__ 
         const int i = (int)(t / h);
         const float ml = lmax[i];
         const float c = (ml > -INFINITY) ? lsum[i] * expf(ml - gmax[i]) / gsum[i] : 0.f;
-        dH[t] += (A[t] * c - ld_as_f32<TB>(Bm + t)) * scale;
+        dH[t] = (OVERWRITE ? 0.f : dH[t]) + (A[t] * c - ld_as_f32<TB>(Bm + t)) * scale;
     }
 }
 
+template <typename TB>
+static void launch_dx_alg2_t(const float* A, const TB* B, const float* lmax, const float* lsum, const float* gmax,
+                             const float* gsum, int h, int64_t total, float scale, bool overwrite, float* dH, int vec,
+                             unsigned blocks, hipStream_t st) {
+    if (overwrite)
+        hipLaunchKernelGGL((dx_alg2_kernel<TB, true>), dim3(blocks), dim3(256), 0, st, A, B, lmax, lsum, gmax, gsum, h,
+                           total, scale, dH, vec);
+    else
+        hipLaunchKernelGGL((dx_alg2_kernel<TB, false>), dim3(blocks), dim3(256), 0, st, A, B, lmax, lsum, gmax, gsum, h,
+                           total, scale, dH, vec);
+}
+
 hipError_t launch_dx_alg2(const float* A, const void* B, int b_is_bf16, const float* lmax, const float* lsum,
-                          const float* gmax, const float* gsum, int N, int h, float scale, float* dH,
+                          const float* gmax, const float* gsum, int N, int h, float scale, bool overwrite, float* dH,
                           hipStream_t st) {
     ProfScope prof(K_DX_ALG2, st);
     const int vec = (h % 4 == 0) ? 1 : 0;
     const int64_t total = vec ? (int64_t)N * (h / 4) : (int64_t)N * h;
     const unsigned blocks = (unsigned)ceil_div(total, 256);
     if (b_is_bf16)
-        hipLaunchKernelGGL((dx_alg2_kernel<u16>), dim3(blocks), dim3(256), 0, st, A, (const u16*)B, lmax, lsum, gmax, gsum,
-                           h, total, scale, dH, vec);
+        launch_dx_alg2_t<u16>(A, (const u16*)B, lmax, lsum, gmax, gsum, h, total, scale, overwrite, dH, vec, blocks, st);
     else
-        hipLaunchKernelGGL((dx_alg2_kernel<float>), dim3(blocks), dim3(256), 0, st, A, (const float*)B, lmax, lsum, gmax,
-                           gsum, h, total, scale, dH, vec);
+        launch_dx_alg2_t<float>(A, (const float*)B, lmax, lsum, gmax, gsum, h, total, scale, overwrite, dH, vec, blocks, st);
     return hipGetLastError();
 }
 

@@ -10,6 +10,7 @@ once, when the plan is built; a step allocates nothing.
 """
 from __future__ import annotations
 
+import contextlib
 from dataclasses import dataclass
 from typing import List, Optional
 
@@ -94,13 +95,22 @@ class OutputLayerPlan:
         self.Bm = [torch.empty((N, h), dtype=H.dtype, device=dev) for _ in range(p)] if algorithm == 2 else None
         self.workspace = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
 
+    def _on(self, stream):
+        """Context in which torch-side fills run on the same stream as the library's kernels."""
+        if stream is None:
+            return contextlib.nullcontext()
+        if not isinstance(stream, torch.cuda.Stream):
+            stream = torch.cuda.ExternalStream(int(stream))
+        return torch.cuda.stream(stream)
+
     def forward(self, stream=None) -> None:
         for r in range(self.p):
             v = self.valid[r]
             if v == 0:     # all padding: the neutral element of the combine (exp(-inf) = 0)
-                self.local_max[r].fill_(float("-inf"))
-                self.local_sumexp[r].zero_()
-                self.local_target[r].zero_()
+                with self._on(stream):
+                    self.local_max[r].fill_(float("-inf"))
+                    self.local_sumexp[r].zero_()
+                    self.local_target[r].zero_()
                 continue
             lg = self.logits[r] if self.logits is not None else None
             if self.algorithm == 1:
@@ -114,19 +124,26 @@ class OutputLayerPlan:
         B.vp_combine_stats(self.local_max, self.local_sumexp, self.local_target,
                            self.global_max, self.global_sumexp, self.loss_rows, self.loss, stream)
         if self.algorithm == 2:
-            # still inside the one barrier of Algorithm 2: the input gradient leaves here
-            self.dH.zero_()
+            # still inside the one barrier of Algorithm 2: the input gradient leaves here; the first shard
+            # that contributes overwrites dH, so nothing is zero-filled
+            first = True
             for r in range(self.p):
                 if self.valid[r] > 0:
                     B.vp_output_dx_alg2(self.A[r], self.Bm[r], self.local_max[r], self.local_sumexp[r],
-                                        self.global_max, self.global_sumexp, self.grad_scale, self.dH, stream)
+                                        self.global_max, self.global_sumexp, self.grad_scale, self.dH, stream,
+                                        dh_overwrite=first)
+                    first = False
+            if first:      # no shard holds a real vocabulary row (cannot happen: vocab_size > 0)
+                with self._on(stream):
+                    self.dH.zero_()
 
     def backward(self, stream=None) -> None:
         first = True      # the first shard that contributes overwrites dH (Algorithm 1): no zero-fill
         for r in range(self.p):
             v = self.valid[r]
             if v < self.rows[r]:
-                self.dW[r][v:].zero_()
+                with self._on(stream):
+                    self.dW[r][v:].zero_()
             if v == 0:
                 continue
             B.vp_output_bwd(self.H, self.W[r][:v], self.labels, self.offsets[r], self.global_max, self.global_sumexp,

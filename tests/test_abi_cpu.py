@@ -105,9 +105,10 @@ def test_argument_validation_launches_nothing(lib):
     assert fwd2(P, P, P, 8, 8, 8, 0, 1, 0, P, P, P, None, P, None, P, 1 << 20, None) == VP_ERR_INVALID_ARG   # no B
     assert fwd2(P, P, P, 8, 8, 8, 0, 1, 2, P, P, P, None, P, P, P, 1 << 20, None) == VP_ERR_INVALID_ARG      # bad flag
     assert fwd2(P, P, P, 8, 8, 8, 0, 1, 0, P, P, P, None, P, P, P, 64, None) == VP_ERR_WORKSPACE
-    assert dx2(P, P, P, P, P, P, 8, 8, 1, 1.0, None, None) == VP_ERR_INVALID_ARG
-    assert dx2(P, P, P, P, P, P, 0, 8, 1, 1.0, P, None) == VP_ERR_INVALID_ARG
-    assert dx2(P, P + 4, P, P, P, P, 8, 8, 1, 1.0, P, None) == VP_ERR_INVALID_ARG
+    assert dx2(P, P, P, P, P, P, 8, 8, 1, 0, 1.0, None, None) == VP_ERR_INVALID_ARG
+    assert dx2(P, P, P, P, P, P, 0, 8, 1, 0, 1.0, P, None) == VP_ERR_INVALID_ARG
+    assert dx2(P, P + 4, P, P, P, P, 8, 8, 1, 0, 1.0, P, None) == VP_ERR_INVALID_ARG
+    assert dx2(P, P, P, P, P, P, 8, 8, 1, 2, 1.0, P, None) == VP_ERR_INVALID_ARG                            # only VP_DH_OVERWRITE
     assert bwd(P, P, P, 8, 8, 8, 0, 1, 2, P, P, None, 1.0, None, P, P, 8, None) == VP_ERR_WORKSPACE          # VP_SKIP_DH: dH may be NULL
     assert bwd(P, P, P, 8, 8, 8, 0, 1, 8, P, P, None, 1.0, P, P, P, 1 << 20, None) == VP_ERR_INVALID_ARG
     assert bwd(P, P, P, 8, 8, 8, 0, 1, 6, P, P, None, 1.0, P, P, P, 1 << 20, None) == VP_ERR_INVALID_ARG      # skip + overwrite

@@ -146,3 +146,62 @@ def test_algorithm2_equals_algorithm1_on_the_gpu():
         assert torch.equal(x, y)         # pass T forms D and dW identically in both algorithms
     # dH: D W (D rounded to bf16) against A c - B (softmax' rounded to bf16): same bar, not the same bits
     assert rel_max_err(to_host(b.dH).astype(np.float64), to_host(a.dH).astype(np.float64)) <= 1e-2
+
+
+# ------------------------------------------------------------------ barrier on a side stream
+def test_barrier_on_a_side_stream_matches_the_serial_order():
+    # The paper overlaps its barriers with compute by putting them on separate streams.  Here the barrier's
+    # on-device work (vp_combine_stats) runs on a second stream of default priority while a pass-S launch of
+    # another microbatch runs on the main stream; both must give bit for bit what the serial order gives.
+    import paper_2411_05288_amd as vp
+    H, Ws, labels = si.small_output_case(2048, 512, 4096, 2, "bf16", seed=71, w_std=0.05)
+    plan = vp.driver.OutputLayerPlan(to_dev(H), [to_dev(w) for w in Ws], to_dev(labels), True)
+    plan.forward()
+    torch.cuda.synchronize()
+    serial = [t.clone() for t in (plan.global_max, plan.global_sumexp, plan.loss_rows, plan.loss,
+                                  plan.local_max, plan.local_sumexp, plan.local_target, plan.logits[0])]
+    # the barrier reads its own copies of the statistics, the concurrent pass S writes fresh buffers
+    lm, ls, lt = plan.local_max.clone(), plan.local_sumexp.clone(), plan.local_target.clone()
+    f32 = dict(dtype=torch.float32, device="cuda")
+    N = plan.N
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()          # default priority
+    for it in range(4):
+        gm, gs, lr, lo = (torch.full((N,), 7.0, **f32), torch.full((N,), 7.0, **f32), torch.full((N,), 7.0, **f32),
+                          torch.full((1,), 7.0, **f32))
+        m2, s2, t2 = torch.full((N,), 7.0, **f32), torch.full((N,), 7.0, **f32), torch.full((N,), 7.0, **f32)
+        y2 = torch.zeros_like(plan.logits[0])
+        side.wait_stream(main)
+        vp.vp_combine_stats(lm, ls, lt, gm, gs, lr, lo, side)
+        vp.vp_output_fwd(plan.H, plan.W[0], plan.labels, 0, m2, s2, t2, y2, plan.workspace)      # main stream
+        main.wait_stream(side)
+        torch.cuda.synchronize()
+        for got, want in zip((gm, gs, lr, lo), serial[:4]):
+            assert torch.equal(got, want), "barrier on the side stream differs from the serial order (iteration %d)" % it
+        assert torch.equal(m2, serial[4][0]) and torch.equal(s2, serial[5][0]) and torch.equal(t2, serial[6][0])
+        assert torch.equal(y2, serial[7])
+
+
+def test_plan_on_an_explicit_stream_orders_its_own_fills():
+    # a plan driven on a stream that is not torch's current one: the torch-side fills (padding rows of dW,
+    # the neutral statistics of an all-padding shard) must be ordered with the library's kernels on that stream
+    import paper_2411_05288_amd as vp
+    H = si.normal((70, 64), 1.0, "bf16", 43, si.STREAM_H)
+    W = si.normal((512, 64), 0.08, "bf16", 43, si.STREAM_W)
+    labels = si.uniform_ids(70, 300, 43)
+    Ws = [np.ascontiguousarray(W[r * 128:(r + 1) * 128]) for r in range(4)]
+    ref = oc.output_layer(si.as_f64(H), si.as_f64(W[:300]), labels)
+    for algorithm in (1, 2):
+        plan = vp.driver.OutputLayerPlan(to_dev(H), [to_dev(w) for w in Ws], to_dev(labels), True, vocab_size=300,
+                                         algorithm=algorithm)
+        for w in plan.dW:
+            w.fill_(5.0)
+        plan.dH.fill_(5.0)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        plan.step(side)
+        side.synchronize()
+        dW = np.concatenate([to_host(w).astype(np.float64) for w in plan.dW])
+        assert rel_max_err(dW[:300], ref["dW"]) <= GRAD_TOL["bf16"] and (dW[300:] == 0).all()
+        assert rel_max_err(to_host(plan.dH).astype(np.float64), ref["dX"]) <= GRAD_TOL["bf16"]
+        assert abs(float(to_host(plan.loss)[0]) - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])

@@ -87,10 +87,15 @@ def test_unscaled_gradients_and_large_logits():
     # grad_scale = 1 is the paper's unscaled form; W scaled so that |Y| reaches ~150,
     # where an unshifted exp would overflow fp32
     H, Ws, labels = si.small_output_case(96, 64, 768, 3, "f32", seed=5, w_std=5.0)
-    assert np.abs(si.as_f64(H) @ si.as_f64(np.concatenate(Ws)).T).max() > 100
-    # one fp32 ulp of a logit of magnitude 150 is 1.5e-5 and enters exp() directly, so the
-    # 1e-5 bar of the benign configurations cannot hold here; 1e-4 bounds what fp32 allows
-    check_against_oracle(H, Ws, labels, True, grad_scale=1.0, tag="large-logits f32", grad_tol=1e-4)
+    ymax = float(np.abs(si.as_f64(H) @ si.as_f64(np.concatenate(Ws)).T).max())
+    assert ymax > 100
+    # Derived bar.  An fp32 logit of magnitude |Y| carries an absolute error eps of a few ulp(|Y|); to first
+    # order a perturbation of the logits of a row by at most eps changes softmax_j by at most 2 eps softmax_j
+    # (d softmax_j = softmax_j (dY_j - sum_k softmax_k dY_k)), hence dH and dW by at most 2 eps of their
+    # magnitude.  With eps = 2 ulp_fp32(|Y|max) that is 4 ulp on top of the 1e-5 of the benign configurations
+    # (ulp(150) = 1.5e-5: about 7e-5 here; 1.1e-5 is what the kernels achieve).
+    grad_tol = 1e-5 + 4.0 * float(np.spacing(np.float32(ymax)))
+    check_against_oracle(H, Ws, labels, True, grad_scale=1.0, tag="large-logits f32", grad_tol=grad_tol)
     H, Ws, labels = si.small_output_case(96, 64, 768, 3, "bf16", seed=5, w_std=2.0)
     plan = run_output_layer(H, Ws, labels, False, 1.0)
     assert np.isfinite(to_host(plan.dH)).all() and np.isfinite(to_host(plan.loss)).all()
@@ -138,12 +143,16 @@ def test_stored_and_recomputed_logits_agree():
     assert rel_max_err(to_host(a.dH).astype(np.float64), to_host(b.dH).astype(np.float64)) < 1e-2
 
 
-def test_generic_gemm_kernel_on_aligned_shapes(monkeypatch):
+def test_generic_gemm_kernel_on_aligned_shapes():
     # aligned shapes normally take the fast kernel; the generic one must give the same answers
-    monkeypatch.setenv("VP_FORCE_GENERIC_GEMM", "1")
-    H, Ws, labels = si.small_output_case(300, 128, 1040, 2, "bf16", seed=3, w_std=0.08)
-    check_against_oracle(H, Ws, labels, True, tag="generic kernel, stored logits")
-    check_against_oracle(H, Ws, labels, False, tag="generic kernel, recompute")
+    import paper_2411_05288_amd as vp
+    vp.vp_profile_force_generic_gemm(True)
+    try:
+        H, Ws, labels = si.small_output_case(300, 128, 1040, 2, "bf16", seed=3, w_std=0.08)
+        check_against_oracle(H, Ws, labels, True, tag="generic kernel, stored logits")
+        check_against_oracle(H, Ws, labels, False, tag="generic kernel, recompute")
+    finally:
+        vp.vp_profile_force_generic_gemm(False)
 
 
 def test_step_can_be_captured_in_a_hip_graph():
