@@ -96,6 +96,28 @@ vp_status vp_output_fwd(const void* H, const void* W_shard, const int64_t* label
                         void* logits_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * vp_output_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops that evaluate a loss, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as vp_output_fwd, except that the scratch (the per-column-tile partial
+ * statistics; with VP_F32 the logits when they are not kept, and K-slice partials) lives in a static device
+ * array inside the library, vp_output_fwd_noalloc_max_scratch() bytes (4 MiB) on every GPU the library
+ * runs on, held until the process ends.  The call allocates and frees nothing.
+ *   - A request whose vp_workspace_bytes(VP_CALL_OUTPUT_FWD, ...) exceeds that size returns
+ *     VP_ERR_UNSUPPORTED and launches nothing (bf16: (2 ceil(Vs/256) + 1) * N * 4 bytes, so all five
+ *     benchmark configurations fit).
+ *   - All calls on one GPU share the one array: calls that overlap on a GPU (two streams, two threads)
+ *     race on it.  Calls on one stream are ordered and safe.  The array keeps the last call's contents;
+ *     nothing in it needs to start at zero.
+ *   - The array's device address is looked up on the first call on each device (with that device current).
+ */
+vp_status vp_output_fwd_noalloc(const void* H, const void* W_shard, const int64_t* labels,
+                                int64_t N, int64_t h, int64_t Vs, int64_t shard_offset,
+                                vp_dtype dt, uint32_t flags,
+                                float* local_max, float* local_sumexp, float* local_target,
+                                void* logits_out, void* stream);
+size_t vp_output_fwd_noalloc_max_scratch(void);
+
+/*
  * Barrier C1 of Algorithm 1 (section 4.3) as an on-device fold over the p shards' rows
  * (it stands in for the two all-reduces):
  *     m_i   = max_r m'_{r,i}

@@ -60,6 +60,10 @@ def load_library() -> ctypes.CDLL:
     lib.vp_dlogits_row_stride.argtypes = [i64, c.c_int]
     lib.vp_output_fwd.restype = c.c_int
     lib.vp_output_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i64, c.c_int, u32, vp, vp, vp, vp, vp, sz, vp]
+    lib.vp_output_fwd_noalloc.restype = c.c_int
+    lib.vp_output_fwd_noalloc.argtypes = [vp, vp, vp, i64, i64, i64, i64, c.c_int, u32, vp, vp, vp, vp, vp]
+    lib.vp_output_fwd_noalloc_max_scratch.restype = sz
+    lib.vp_output_fwd_noalloc_max_scratch.argtypes = []
     lib.vp_combine_stats.restype = c.c_int
     lib.vp_combine_stats.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, vp, vp]
     lib.vp_output_bwd.restype = c.c_int
@@ -177,6 +181,30 @@ def vp_output_fwd(H, W_shard, labels, shard_offset: int, local_max, local_sumexp
         _ptr(local_target, "local_target", (torch.float32,), (N,)),
         _ptr(logits_out, "logits_out", same, (N, Vs)), wp, wb, _stream(stream))
     _check(st, "vp_output_fwd")
+
+
+def vp_output_fwd_noalloc(H, W_shard, labels, shard_offset: int, local_max, local_sumexp, local_target,
+                          logits_out=None, stream=None) -> None:
+    """vp_output_fwd with the scratch in a static device array of the library: no workspace argument,
+    nothing allocated.  Sizes whose scratch exceeds vp_output_fwd_noalloc_max_scratch() are refused."""
+    N, h = H.shape
+    Vs = W_shard.shape[0]
+    dt = _dtype_code(H)
+    if _dtype_code(W_shard) != dt or W_shard.shape[1] != h:
+        raise VPError("W_shard must be [Vs, h] with the dtype of H")
+    same = (torch.float32,) if dt == VP_F32 else _BF16_LIKE
+    st = load_library().vp_output_fwd_noalloc(
+        _ptr(H, "H"), _ptr(W_shard, "W_shard"), _ptr(labels, "labels", (torch.int64,), (N,)),
+        N, h, Vs, shard_offset, dt, VP_SAVE_LOGITS if logits_out is not None else 0,
+        _ptr(local_max, "local_max", (torch.float32,), (N,)),
+        _ptr(local_sumexp, "local_sumexp", (torch.float32,), (N,)),
+        _ptr(local_target, "local_target", (torch.float32,), (N,)),
+        _ptr(logits_out, "logits_out", same, (N, Vs)), _stream(stream))
+    _check(st, "vp_output_fwd_noalloc")
+
+
+def vp_output_fwd_noalloc_max_scratch() -> int:
+    return load_library().vp_output_fwd_noalloc_max_scratch()
 
 
 def vp_combine_stats(local_max, local_sumexp, local_target, global_max, global_sumexp, loss_per_row,

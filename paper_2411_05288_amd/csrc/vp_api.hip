@@ -1,5 +1,7 @@
 // extern "C" entry points of libvp: argument validation, workspace carving and the order of
 // kernel launches for each pass.  No allocation, no synchronisation, no state.
+#include <mutex>
+
 #include "vp_internal.h"
 
 using namespace vp;
@@ -40,6 +42,29 @@ size_t f32_bwd_scratch(int64_t N, int64_t h, int64_t Vs) {
 size_t f32_matrix_bytes(int64_t N, int64_t Vs) { return align_up((size_t)N * Vs * sizeof(float), 256); }
 
 vp_status dev(hipError_t e) { return e == hipSuccess ? VP_OK : VP_ERR_DEVICE; }
+
+// Scratch of vp_output_fwd_noalloc: device memory that belongs to the library's code object, so the
+// entry point has nothing to allocate.  Every GPU the library runs on holds its own copy until the
+// process ends.  In host code the array's name is only a handle: its device address is looked up
+// once per device (with that device current) and that address is what the kernels are given.
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)4 << 20;
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[NOALLOC_MAX_DEVICES] = {nullptr};
+
+// Device address of `scratch` on the current device, nullptr if the runtime refuses.
+void* scratch_of_current_device() {
+    int d = -1;
+    if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= NOALLOC_MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[d]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[d] = ptr;
+    }
+    return g_scratch_ptr[d];
+}
 
 }  // namespace
 
@@ -138,6 +163,25 @@ vp_status vp_output_fwd(const void* H, const void* W_shard, const int64_t* label
     if (e != hipSuccess) return VP_ERR_DEVICE;
     return dev(launch_row_stats_f32(Y, Vs, labels, shard_offset, (int)N, (int)Vs, local_max, local_sumexp,
                                     local_target, st));
+}
+
+size_t vp_output_fwd_noalloc_max_scratch(void) { return NOALLOC_SCRATCH_BYTES; }
+
+vp_status vp_output_fwd_noalloc(const void* H, const void* W_shard, const int64_t* labels, int64_t N, int64_t h,
+                                int64_t Vs, int64_t shard_offset, vp_dtype dt, uint32_t flags, float* local_max,
+                                float* local_sumexp, float* local_target, void* logits_out, void* stream) {
+    // sizes first: a request whose scratch does not fit the static array is refused before anything else
+    if (!sizes_ok(N, h, Vs) || !dtype_ok(dt)) return VP_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)VP_SAVE_LOGITS) return VP_ERR_INVALID_ARG;
+    if (!sizes_supported(N, h, Vs)) return VP_ERR_UNSUPPORTED;
+    const size_t need = vp_workspace_bytes(VP_CALL_OUTPUT_FWD, N, h, Vs, dt, flags);
+    if (need == (size_t)-1 || need > NOALLOC_SCRATCH_BYTES) return VP_ERR_UNSUPPORTED;
+    void* ws = scratch_of_current_device();
+    if (!ws) return VP_ERR_DEVICE;
+    // nothing in the scratch has to start at zero: every partial the fold reads is written by this call's
+    // GEMM first (the target partial only for rows whose label the shard owns, and only those are read)
+    return vp_output_fwd(H, W_shard, labels, N, h, Vs, shard_offset, dt, flags, local_max, local_sumexp, local_target,
+                         logits_out, ws, NOALLOC_SCRATCH_BYTES, stream);
 }
 
 vp_status vp_combine_stats(const float* local_max, const float* local_sumexp, const float* local_target, int32_t p,
