@@ -3,12 +3,14 @@
 
 A step is one pass of the whole path over one batch of synthetic input:
 p x vp_output_fwd, vp_combine_stats, p x vp_output_bwd (all p shards of the configuration run
-in sequence on the one GPU).  The headline workload is the Llama-like configuration
-(N=4096, h=4096, V=32000, p=8, bf16); the other configurations are timed briefly as well and
-reported under "per_config".  Inputs are resident in HBM before the timed region starts.
+in sequence on the one GPU).  The headline workload is the largest configuration, cfg4
+(N=4096, h=8192, V=256000, p=16, bf16, logits recomputed in the backward pass); the other
+configurations are timed briefly as well and reported under "per_config", each with its own
+roofline entry.  Inputs are resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  value = 6*N*h*V / step time (the paper's FLOP model for the output
-layer), in TFLOP/s.
+layer, appendix A), in TFLOP/s.  With recomputed logits the hardware executes 8*N*h*V flops per
+step; that rate is reported next to it as "hardware_tflops" and is never the headline value.
 """
 from __future__ import annotations
 
@@ -26,12 +28,13 @@ import numpy as np  # noqa: E402
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
-# HBM-side traffic per launch of the GEMM kernels, from two rocprofv3 --pmc runs of this file
-# (FETCH_SIZE, WRITE_SIZE in KiB per dispatch; summaries in profiles/output_layer_<config>.txt).
-# A plain 256 MiB copy in the same runs reads 0.5x its size on FETCH_SIZE and 1.0x on
-# WRITE_SIZE, hence the factors.  Counters cannot be read from inside this process.
+# L2-miss / fabric traffic per launch of the GEMM kernels: what leaves the eight L2s towards the memory-side
+# cache and HBM.  NOT measured by this run (counters cannot be read from inside the process): the figures
+# are copied from the committed rocprofv3 --pmc summaries (FETCH_SIZE, WRITE_SIZE in KiB per dispatch;
+# profiles/output_layer_<config>.txt, which state the command).  A plain 256 MiB copy in the same counter
+# runs reads 0.5x its size on FETCH_SIZE and 1.0x on WRITE_SIZE, hence the factors.
 PMC_FETCH_FACTOR, PMC_WRITE_FACTOR = 2.0, 1.0
-PMC_KIB = {   # kernel -> (FETCH_SIZE, WRITE_SIZE); dH is the accumulating launch (7 of 8 shards; the first one writes)
+PMC_KIB = {   # kernel -> (FETCH_SIZE, WRITE_SIZE); dH is the accumulating launch (all shards but the first)
     "cfg2_llama": {"gemm_bf16_fwd_stats": (100811.7, 36882.1), "gemm_bf16_dH": (134515.7, 66816.0),
                    "gemm_bf16_dW": (98481.1, 64000.0)},
     "cfg3_large_vocab": {"gemm_bf16_fwd_stats": (482860.5, 143630.4), "gemm_bf16_dH": (459801.5, 66816.0),
@@ -84,16 +87,18 @@ def profiled_steps(vp, step, steps):
             for k, (ms, n) in rec.items()}
 
 
-def make_output_plan(vp, cfg, seeded_numpy, algorithm=1):
+def make_output_plan(vp, cfg, seeded_numpy, algorithm=1, host=None):
     """Inputs of an output-layer configuration in HBM.  seeded_numpy=True uses the host
-    generator shared with the oracle tests; otherwise tensors of the same distribution are
-    drawn on the GPU (only timed, never compared)."""
+    generator shared with the oracle tests (host = (H, [W_r]) if the caller has drawn them already);
+    otherwise tensors of the same distribution are drawn on the GPU (only timed, never compared)."""
     import torch
     import synth_inputs as si
     labels = si.make_labels(cfg)
     if seeded_numpy:
-        H = dev(si.make_H(cfg))
-        Ws = [dev(si.make_W_shard(cfg, r)) for r in range(cfg.p)]
+        if host is None:
+            host = (si.make_H(cfg), [si.make_W_shard(cfg, r) for r in range(cfg.p)])
+        H = dev(host[0])
+        Ws = [dev(w) for w in host[1]]
     else:
         g = torch.Generator(device="cuda")
         g.manual_seed(si.BASE_SEED)
@@ -126,14 +131,33 @@ def gemm_roofline(cfg, kernels):
     ach = flops_per_launch / (kernels[dom]["ms_per_launch"] * 1e-3) / 1e12
     pmc = PMC_KIB.get(cfg.name, {}).get(dom)
     traffic = None if pmc is None else (PMC_FETCH_FACTOR * pmc[0] + PMC_WRITE_FACTOR * pmc[1]) * 1024.0
+    # algorithmic bytes of one launch: both operands read once, the output written once (dH += also reads it)
+    ab = {"gemm_bf16_fwd_stats": 2.0 * (cfg.N * cfg.h + cfg.Vs * cfg.h) + (2.0 * cfg.N * cfg.Vs if cfg.save_logits else 0.0),
+          "gemm_bf16_dlogits": 2.0 * (cfg.N * cfg.h + cfg.Vs * cfg.h) + 2.0 * cfg.N * cfg.Vs,
+          "gemm_bf16_dH": 2.0 * (cfg.N * cfg.Vs + cfg.Vs * cfg.h) + 8.0 * cfg.N * cfg.h,
+          "gemm_bf16_dW": 2.0 * (cfg.N * cfg.Vs + cfg.N * cfg.h) + 4.0 * cfg.Vs * cfg.h}.get(dom)
     return {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": ach / BF16_MFMA_PEAK_TFLOPS, "flops_per_launch": flops_per_launch,
-            "avg_launch_ms": kernels[dom]["ms_per_launch"], "traffic": traffic, "traffic_unit": "bytes per launch"}
+            "avg_launch_ms": kernels[dom]["ms_per_launch"], "traffic": traffic, "traffic_unit": "bytes per launch",
+            "traffic_kind": "L2-miss / fabric bytes (2.0 x FETCH_SIZE + WRITE_SIZE)",
+            "traffic_source": None if pmc is None else
+            "not measured by this run: copied from the committed counter summary profiles/output_layer_%s.txt" % cfg.name,
+            "algorithmic_bytes_per_launch": ab}
 
 
-def cpu_baseline(cfg, sample_rows):
+def cpu_sample_rows(cfg, requested):
+    """Token rows of the CPU leg: all of them when the oracle's step is below about 10 TFLOP of fp64 work
+    (some 10-30 s on the host of a GPU machine), else the largest multiple of 256 rows that is."""
+    if requested > 0:
+        return min(requested, cfg.N)
+    rows = int(10e12 / (6.0 * cfg.h * cfg.V)) // 256 * 256
+    return min(cfg.N, max(256, rows))
+
+
+def cpu_baseline(cfg, sample_rows, host):
     """The oracle (Algorithm 1 on the CPU, fp64) on the first `sample_rows` token rows of the
-    same inputs, all p shards, forward and backward."""
+    same inputs, all p shards, forward and backward.  The rate does not depend on the number of rows
+    (every row costs 6 h V flops), so a sample gives the full workload's rate without extrapolation."""
     import synth_inputs as si
     from oracle import vp_oracle as oc
     try:
@@ -141,18 +165,19 @@ def cpu_baseline(cfg, sample_rows):
         cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    sample_rows = cfg.N if sample_rows <= 0 else min(sample_rows, cfg.N)
-    H = si.as_f64(si.make_H(cfg)[:sample_rows])
+    sample_rows = cpu_sample_rows(cfg, sample_rows)
+    H = si.as_f64(host[0][:sample_rows])
     labels = si.make_labels(cfg)[:sample_rows]
-    Ws = [si.as_f64(si.make_W_shard(cfg, r)) for r in range(cfg.p)]
+    Ws = [si.as_f64(w) for w in host[1]]
     t0 = time.perf_counter()
     out = oc.output_layer_alg1(H, Ws, labels)
     dt = time.perf_counter() - t0
     flops = 6.0 * sample_rows * cfg.h * cfg.V
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
             "seconds": dt, "loss_on_sample": float(out["loss"]),
-            "sample": "oracle.output_layer_alg1 (fp64) on the first %d of %d token rows of %s, all %d shards, "
-                      "forward + backward" % (sample_rows, cfg.N, cfg.name, cfg.p)}
+            "sample": "oracle.output_layer_alg1 (NumPy fp64) on the first %d of %d token rows of %s, all %d shards, "
+                      "forward + backward (%.1f TFLOP of the step's %.1f)" % (
+                          sample_rows, cfg.N, cfg.name, cfg.p, flops / 1e12, cfg.model_flops / 1e12)}
 
 
 def bench_embedding(vp, cfg, steps, warmup):
@@ -186,36 +211,48 @@ def bench_embedding(vp, cfg, steps, warmup):
                      "frac": fwd_bytes / cfg.p / (kern["embed_fwd"]["ms_per_launch"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "bytes_per_launch": fwd_bytes / cfg.p, "avg_launch_ms": kern["embed_fwd"]["ms_per_launch"],
                      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 per launch (profiles/input_layer_cfg5_embedding.txt)
-                     "traffic": (2.0 * 2524.4 + 65564.3) * 1024.0, "traffic_unit": "bytes per launch"},
+                     "traffic": (2.0 * 2524.4 + 65564.3) * 1024.0, "traffic_unit": "bytes per launch",
+                     "traffic_kind": "L2-miss / fabric bytes (2.0 x FETCH_SIZE + WRITE_SIZE)",
+                     "traffic_source": "not measured by this run: copied from the committed counter summary "
+                                       "profiles/input_layer_cfg5_embedding.txt"},
     }
 
 
 def mfma_sustained(vp, cfg):
     """What the matrix cores sustain with no memory traffic at all, for operands distributed like this
-    configuration's H and W (and, for contrast, for zeros): the power-limited ceiling of any bf16 GEMM
-    on these values.  TFLOP/s."""
+    configuration's H and W (and, for contrast, for zeros), over the instruction shapes and issue orders of
+    vp_profile_mfma_variant: the power-limited envelope of any bf16 GEMM on these values.  TFLOP/s."""
     import torch
-    iters, blocks = 4096, 256
+    blocks = 256
     out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
-    flops = blocks * 4 * iters * 16 * 2.0 * 32 * 32 * 16
     g = torch.Generator(device="cuda")
     g.manual_seed(7)
-    n = 8 * 256 * 8
-    half = n // 2
-    hw = torch.cat([torch.randn(half, generator=g, device="cuda") * cfg.h_std,
-                    torch.randn(half, generator=g, device="cuda") * cfg.w_std]).to(torch.bfloat16)
+    frags = 32
+    x = torch.randn(frags, 256 * 8, generator=g, device="cuda")
+    # fragments 0-3 of every group of 8 feed one operand (values like H), 4-7 the other (values like W)
+    std = torch.tensor([cfg.h_std if (f % 8) < 4 else cfg.w_std for f in range(frags)], device="cuda")[:, None]
+    hw = (x * std).to(torch.bfloat16).contiguous().view(-1)
+    zeros = torch.zeros_like(hw)
+    names = ["32x32x16 by columns", "32x32x16 snake", "32x32x16 k-chain of 2", "32x32x16 k-chain of 4",
+             "16x16x32 by columns", "16x16x32 snake"]
     res = {}
-    for name, src in (("operands_like_H_and_W", hw), ("zero_operands", torch.zeros(n, dtype=torch.bfloat16, device="cuda"))):
-        for _ in range(5):
-            vp.vp_profile_mfma_loop(src, out, iters, blocks)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(20):
-            vp.vp_profile_mfma_loop(src, out, iters, blocks)
-        e1.record()
-        torch.cuda.synchronize()
-        res[name] = flops / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12
+    for label, src in (("operands_like_H_and_W", hw), ("zero_operands", zeros)):
+        per = {}
+        for v in range(vp.vp_profile_mfma_variant_count()):
+            iters = 4096 // (1 if v < 2 else (2 if v == 2 else 4))
+            for _ in range(3):
+                vp.vp_profile_mfma_variant(src, out, iters, blocks, v)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = 0.0
+            for _ in range(10):
+                flops += vp.vp_profile_mfma_variant(src, out, iters, blocks, v)
+            e1.record()
+            torch.cuda.synchronize()
+            per[names[v]] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        res[label] = per
+    res["envelope_like_H_and_W"] = max(res["operands_like_H_and_W"].values())
     return res
 
 
@@ -329,13 +366,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="cfg2_llama", help="headline output-layer configuration")
+    ap.add_argument("--config", default="cfg4_very_large_vocab", help="headline output-layer configuration")
     ap.add_argument("--only-headline", action="store_true", help="skip the per_config section")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 256 MiB (read 256 MiB, write 256 MiB) five times, so "
                          "that a counter run of this command carries a kernel of known HBM traffic")
-    ap.add_argument("--cpu-sample-rows", type=int, default=0, help="0 = all token rows of the workload")
+    ap.add_argument("--cpu-sample-rows", type=int, default=0,
+                    help="token rows of the CPU leg; 0 = as many as keep the oracle near 10 TFLOP of work")
     ap.add_argument("--timeline", action="store_true",
                     help="only print the itemised per-launch time budget (prologue / main loop / epilogue / idle) of "
                          "the GEMM kernels of --config, from the kernel's own phase stamps")
@@ -374,7 +412,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    plan = make_output_plan(vp, cfg, seeded_numpy=True)
+    host = (si.make_H(cfg), [si.make_W_shard(cfg, r) for r in range(cfg.p)])
+    plan = make_output_plan(vp, cfg, seeded_numpy=True, host=host)
     wall_ms, ev_ms = time_steps(plan.step, args.steps, args.warmup)
     kernels = profiled_steps(vp, plan.step, args.steps)
     nums = output_numbers(cfg, wall_ms)
@@ -398,21 +437,24 @@ def main():
             per_config[name] = dict(output_numbers(c, w_ms), kernels=kern, roofline=gemm_roofline(c, kern))
             del pl
             torch.cuda.empty_cache()
-        # the same headline workload through Algorithm 2 (one barrier; same three products per shard)
-        pl = make_output_plan(vp, cfg, seeded_numpy=False, algorithm=2)
+        # the Llama-like workload through Algorithm 2 (one barrier; same three products per shard), and the
+        # barrier on a side stream next to a pass S of that workload
+        c2 = si.CONFIGS["cfg2_llama"]
+        pl = make_output_plan(vp, c2, seeded_numpy=False, algorithm=2)
         k_steps = max(3, min(args.steps, 10))
         w_ms, _ = time_steps(pl.step, k_steps, 2)
         kern = profiled_steps(vp, pl.step, k_steps)
-        per_config[cfg.name + "_algorithm2"] = dict(output_numbers(cfg, w_ms), kernels=kern)
+        per_config[c2.name + "_algorithm2"] = dict(output_numbers(c2, w_ms), kernels=kern)
         del pl
         torch.cuda.empty_cache()
-        per_config["barrier_overlap_" + cfg.name] = bench_barrier_overlap(vp, cfg, 50)
+        per_config["barrier_overlap_" + c2.name] = bench_barrier_overlap(vp, c2, 50)
         torch.cuda.empty_cache()
 
     roof = gemm_roofline(cfg, kernels)
     if roof is not None:
         # context for frac: the MFMA-only rate this chip sustains on such operand values (power limited)
         roof["mfma_only_sustained_tflops"] = mfma_sustained(vp, cfg)
+        roof["frac_of_sustained_envelope"] = roof["achieved"] / roof["mfma_only_sustained_tflops"]["envelope_like_H_and_W"]
     out = {
         "metric": METRIC,
         "value": nums["model_tflops"],
@@ -430,6 +472,8 @@ def main():
         "tokens_per_s": nums["tokens_per_s"],
         "tokens_per_s_per_shard_device": nums["tokens_per_s_per_shard_device"],
         "pct_bf16_mfma_peak": nums["pct_bf16_mfma_peak"],
+        "hardware_tflops": nums["hardware_tflops"],
+        "pct_bf16_mfma_peak_hardware_flops": 100.0 * nums["hardware_tflops"] / BF16_MFMA_PEAK_TFLOPS,
         "loss": loss,
         "config": {"workload": "%s: N=%d h=%d V=%d p=%d Vs=%d %s, logits %s; fwd + combine + bwd of all p shards "
                                "in sequence on one GPU" % (cfg.name, cfg.N, cfg.h, cfg.V, cfg.p, cfg.Vs, cfg.dtype,
@@ -438,7 +482,7 @@ def main():
                    "model_flops_per_step": cfg.model_flops},
         "roofline": roof,
         "kernels": kernels,
-        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(cfg, args.cpu_sample_rows),
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(cfg, args.cpu_sample_rows, host),
         "per_config": per_config,
     }
     print(json.dumps(out))
