@@ -1,6 +1,9 @@
 // Fast path of the bf16 MFMA GEMM (gfx950): operands go from global memory straight into LDS
-// (buffer loads with the LDS bit, 16 bytes per lane), two 64 KB LDS stages, MFMA operands
-// prefetched one 16-wide k sub-step ahead, one workgroup barrier per 64-wide k step.
+// (buffer loads with the LDS bit, 16 bytes per lane) through a ring of five half-k-tile slots,
+// MFMA operands are prefetched one 16-wide k sub-step ahead, two workgroup barriers per 64-wide
+// k tile.  The loads of a k tile are in flight for a whole tile period before anything waits for
+// them: with one wavefront per SIMD nothing else hides the load latency (about 0.9 us under load,
+// longer than the matrix cores need for a tile at any clock this part sustains).
 //
 // Preconditions (checked by gemm_bf16_fast_ok on the host; anything else takes the generic
 // kernel): rows of both operands 16-byte aligned, operands smaller than 4 GB with slack for
@@ -16,14 +19,13 @@
 // other operand (k tails; this is why K % 64 == 0 is required when no operand is K-strided)
 // or lands in output rows / columns that the epilogue never stores.
 //
-// LDS layouts (each operand tile is 32 KB, written by 32 wave-wide loads of 1 KB; a load
-// writes lane i's 16 bytes at byte 16*i of its 1 KB slot, so the swizzles below are applied to
-// the global address each lane fetches):
-//   K-contiguous tile  [256 rows][64 k]: 128 B rows; 16-byte chunk c of row r sits at chunk
-//       position c ^ ((r >> 1) & 7).  One ds_read_b128 per MFMA operand.  The LDS serves a
-//       ds_read_b128 in passes of 16 lanes over 64 banks, and the lanes of a pass are not
-//       consecutive (measured: XOR with r & 7 costs 1.67x, XOR with (r >> 1) & 7 is conflict free).
-//   K-strided tile [64 k][256 rows]: 512 B k-rows of 16 segments of 32 B (16 rows); segment s of
+// LDS layouts (a slot holds 32 of a k tile's 64 k for both operands, 16 KB each, written by 16
+// wave-wide loads of 1 KB per operand; a load writes lane i's 16 bytes at byte 16*i of its 1 KB
+// piece, so the swizzles below are applied to the global address each lane fetches):
+//   K-contiguous half  [256 rows][32 k]: 64 B rows; 16-byte chunk c of row r sits at chunk
+//       position c ^ ((r >> 2) & 3).  One ds_read_b128 per MFMA operand; the 16 consecutive rows a
+//       pass of that read serves fall into 16 different bank groups (counter: no bank conflicts).
+//   K-strided half [32 k][256 rows]: 512 B k-rows of 16 segments of 32 B (16 rows); segment s of
 //       k-row k sits at segment position s ^ f(k & 3), f = {0,5,2,7}.  MFMA operands are read
 //       with the transposing LDS load (ds_read_b64_tr_b16): in a group of 16 lanes, lane s
 //       points at k-row kb + s/4, rows nb + 4*(s%4)..+3, and lane i receives rows nb + i for
@@ -38,35 +40,56 @@ namespace vp {
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
-constexpr int TILE_BYTES = 32768;             // one operand tile
-constexpr int STAGE_BYTES_F = 2 * TILE_BYTES; // A tile then B tile
+constexpr int HALF_OP_BYTES = 16384;          // one operand, 32 of the 64 k of a k tile: 256 x 32 bf16
+constexpr int SLOT_BYTES = 2 * HALF_OP_BYTES; // A half then B half
+constexpr int N_SLOTS = 5;
 
-// Two separate arrays: every LDS address of the main loop is then "array base + offset below 64 KB",
-// which fits the 16-bit offset field of the LDS instructions (one array of 128 KB costs address
-// arithmetic in the main loop: measured 25 % slower).  Nothing relies on how the two are placed
-// relative to each other: the epilogue's exchange area and the staging blocks of wavefronts 0 and 1
-// lie in stage 0, the staging blocks of wavefronts 2 and 3 in stage 1.
-__shared__ __attribute__((aligned(1024))) char g_stage0[STAGE_BYTES_F];
-__shared__ __attribute__((aligned(1024))) char g_stage1[STAGE_BYTES_F];
-static_assert(EPI_XCHG_BYTES + 2 * StageF32<128>::BYTES <= STAGE_BYTES_F, "epilogue staging exceeds LDS stage 0");
-static_assert(2 * StageF32<128>::BYTES <= STAGE_BYTES_F, "epilogue staging exceeds LDS stage 1");
+// Five LDS slots of half a k tile each (all 160 KB of the compute unit).  K tile T occupies the slots
+// (2T) % 5 and (2T + 1) % 5, so that next to the two tiles being multiplied and landing there is one
+// spare slot: together with the first half of the running tile, which is free after its first two
+// sub-steps, it takes the two halves of tile T + 2 from the MIDDLE of tile T on.  The global loads of
+// a tile are thus a whole tile period in flight before they are waited for (with two full-tile stages
+// it was half a period: the main loop then ran at "load latency + issue time" per tile, one third
+// below the matrix cores' own time, at any clock).
+//
+// Separate arrays: the compiler orders an LDS read after the direct-to-LDS loads it may alias with by
+// a wait on the memory counter, and tells the arrays apart by their identity - reads of one slot do
+// not wait for loads still in flight to another.  (This also means every LDS access of the main loop
+// must name its slot at compile time: the loop is unrolled over the period of five tiles.)
+__shared__ __attribute__((aligned(1024))) char g_slot0[SLOT_BYTES];
+__shared__ __attribute__((aligned(1024))) char g_slot1[SLOT_BYTES];
+__shared__ __attribute__((aligned(1024))) char g_slot2[SLOT_BYTES];
+__shared__ __attribute__((aligned(1024))) char g_slot3[SLOT_BYTES];
+__shared__ __attribute__((aligned(1024))) char g_slot4[SLOT_BYTES];
+static_assert(EPI_XCHG_BYTES + StageF32<128>::BYTES <= SLOT_BYTES, "epilogue staging exceeds an LDS slot");
 static_assert(StageBf16<128>::BYTES <= StageF32<128>::BYTES, "bf16 staging block larger than the fp32 one");
+
+template <int S>
+__device__ __forceinline__ char* lds_slot() {
+    static_assert(S >= 0 && S < N_SLOTS, "slot");
+    if constexpr (S == 0) return g_slot0;
+    else if constexpr (S == 1) return g_slot1;
+    else if constexpr (S == 2) return g_slot2;
+    else if constexpr (S == 3) return g_slot3;
+    else return g_slot4;
+}
 
 __device__ __forceinline__ int seg_swizzle(int k_low2) { return k_low2 ^ ((k_low2 & 1) << 2); }
 
-// Byte offsets (within the operand's buffer, before the k advance) of the 8 chunks this lane
-// fetches for one operand tile: wave w fills 1 KB slots 8w .. 8w+7 of the tile.
+// Byte offsets (within the operand's buffer, before the k advance) of the 4 chunks this lane fetches
+// for one operand half tile: wave w fills 1 KB pieces 4w .. 4w+3 of the half.  The same offsets serve
+// both halves of a k tile (the half is selected by the descriptor's base).
 template <bool KC>
-__device__ __forceinline__ void tile_voffsets(unsigned (&voff)[8], int r0, int ld, int wave, int lane) {
+__device__ __forceinline__ void half_voffsets(unsigned (&voff)[4], int r0, int ld, int wave, int lane) {
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-        const int slot = wave * 8 + jj;
+    for (int jj = 0; jj < 4; ++jj) {
+        const int piece = wave * 4 + jj;
         if (KC) {
-            const int row = slot * 8 + (lane >> 3);
-            const int c = (lane & 7) ^ ((row >> 1) & 7);
+            const int row = piece * 16 + (lane >> 2);
+            const int c = (lane & 3) ^ ((row >> 2) & 3);
             voff[jj] = ((unsigned)(r0 + row) * (unsigned)ld + (unsigned)(c * 8)) * 2u;
         } else {
-            const int krow = slot * 2 + (lane >> 5);
+            const int krow = piece * 2 + (lane >> 5);
             const int cpos = lane & 31;
             const int seg = (cpos >> 1) ^ seg_swizzle(krow & 3);
             const int c = seg * 2 + (cpos & 1);
@@ -75,37 +98,33 @@ __device__ __forceinline__ void tile_voffsets(unsigned (&voff)[8], int r0, int l
     }
 }
 
-// Loads LO..HI-1 of the 16 wave-wide loads that bring one k tile into a stage (0..7: this
-// wavefront's 1 KB slots of the A tile, 8..15: of the B tile).  The k advance is applied to the
-// descriptor (base += kadv, size -= kadv) rather than to the per-lane offsets: the offsets stay
-// loop invariant, the advance costs a few scalar ops, and the range check still sees the true
-// distance to the end of the operand.  The advance is clamped to the operand size, so a tile
-// index past the end of K yields an empty descriptor (every lane reads zero, no access is made):
-// the main loop may therefore request tiles beyond K without a branch.
-template <int LO, int HI>
-__device__ __forceinline__ void issue_loads(const GemmBf16Params& g, unsigned a_bytes, unsigned b_bytes,
-                                            unsigned a_kadv, unsigned b_kadv, const unsigned (&avoff)[8],
-                                            const unsigned (&bvoff)[8], char* stage, int wave) {
-    a_kadv = a_kadv < a_bytes ? a_kadv : a_bytes;
-    b_kadv = b_kadv < b_bytes ? b_kadv : b_bytes;
-    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)g.A + a_kadv), 0,
-                                                                         (int)(a_bytes - a_kadv), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)g.B + b_kadv), 0,
-                                                                         (int)(b_bytes - b_kadv), 0x00020000);
+// The 8 wave-wide loads that bring this wavefront's share of one operand of k tile `kadv / kstep` in:
+// 4 pieces, each as a pair (first half -> slot S0, second half -> slot S1) issued back to back, so that
+// the two 64-byte halves of a 128-byte line of a K-contiguous operand meet in the vector cache.  The k
+// advance is applied to the descriptors (base += advance, size -= advance, clamped to the operand size:
+// a tile past the end of K yields empty descriptors, every lane reads zero and no access is made), so
+// the per-lane offsets are loop invariant and the range check still sees the true distance to the end.
+template <bool IS_B, int S0, int S1>
+__device__ __forceinline__ void issue_operand_loads(const void* base, unsigned bytes, unsigned kadv, unsigned half_adv,
+                                                    const unsigned (&voff)[4], int wave) {
+    const unsigned adv0 = kadv < bytes ? kadv : bytes;
+    const unsigned adv1 = kadv + half_adv < bytes ? kadv + half_adv : bytes;
+    const __amdgpu_buffer_rsrc_t rs0 = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + adv0), 0,
+                                                                         (int)(bytes - adv0), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs1 = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + adv1), 0,
+                                                                         (int)(bytes - adv1), 0x00020000);
 #pragma unroll
-    for (int idx = LO; idx < HI; ++idx) {
-        if (idx < 8) {
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr)(stage + (wave * 8 + idx) * 1024), 16,
-                                                     (int)avoff[idx], 0, 0, 0);
-        } else {
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr)(stage + TILE_BYTES + (wave * 8 + idx - 8) * 1024),
-                                                     16, (int)bvoff[idx - 8], 0, 0, 0);
-        }
+    for (int jj = 0; jj < 4; ++jj) {
+        const int off = (IS_B ? HALF_OP_BYTES : 0) + (wave * 4 + jj) * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs0, (lds_ptr)(lds_slot<S0>() + off), 16, (int)voff[jj], 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs1, (lds_ptr)(lds_slot<S1>() + off), 16, (int)voff[jj], 0, 0, 0);
     }
 }
 
-// Per-lane LDS byte offsets for operand reads of the wavefront's 128 rows (4 MFMA tiles).
-//  KC: base[kk] = address of (row = wt*128 + l32, chunk (2kk + hf) ^ ((l32 >> 1) & 7)); tile t adds t*4096
+// Per-lane LDS byte offsets for operand reads of the wavefront's 128 rows (4 MFMA tiles) in a half.
+//  KC: 64-byte rows, 16-byte chunk c of row r at chunk position c ^ ((r >> 2) & 3) (16 consecutive rows
+//      with the same chunk then fall into 16 different bank groups).  base[kk] = address of
+//      (row = wt*128 + l32, chunk 2kk + hf); tile t adds t*2048.  base[2], base[3] unused.
 //  KS: base[t]  = address of (k = 8*(b>>1) + s/4, segment of tile t and lane group b, 8*(s&3));
 //                 sub-step kk / half rd adds (16kk + 4rd) * 512
 template <bool KC>
@@ -113,8 +132,9 @@ __device__ __forceinline__ void frag_offsets(int (&base)[4], int wt, int lane) {
     if (KC) {
         const int l32 = lane & 31, hf = lane >> 5;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-            base[kk] = (wt * 128 + l32) * 128 + ((((kk << 1) | hf) ^ ((l32 >> 1) & 7)) << 4);
+        for (int kk = 0; kk < 2; ++kk)
+            base[kk] = (wt * 128 + l32) * 64 + ((((kk << 1) | hf) ^ ((l32 >> 2) & 3)) << 4);
+        base[2] = base[3] = 0;
     } else {
         const int b = lane >> 4, s = lane & 15;
         const int f = seg_swizzle(s >> 2);
@@ -127,12 +147,19 @@ __device__ __forceinline__ void frag_offsets(int (&base)[4], int wt, int lane) {
 }
 
 template <bool KC>
-__device__ __forceinline__ bf16x8 read_operand(const char* tile, const int (&base)[4], int t, int kk) {
+__device__ __forceinline__ void opaque_offsets(int (&base)[4]) {
+    if (KC) asm volatile("" : "+v"(base[0]), "+v"(base[1]));
+    else asm volatile("" : "+v"(base[0]), "+v"(base[1]), "+v"(base[2]), "+v"(base[3]));
+}
+
+// kk: sub-step within the half (0 or 1)
+template <bool KC>
+__device__ __forceinline__ bf16x8 read_operand(const char* half, const int (&base)[4], int t, int kk) {
     if (KC) {
-        return *reinterpret_cast<const bf16x8*>(tile + base[kk] + t * 4096);
+        return *reinterpret_cast<const bf16x8*>(half + base[kk] + t * 2048);
     } else {
         union { short4v h[2]; bf16x8 v; } u;
-        const char* p = tile + base[t] + kk * 8192;
+        const char* p = half + base[t] + kk * 8192;
         u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(p));
         u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(p + 2048));
         return u.v;
@@ -140,18 +167,18 @@ __device__ __forceinline__ bf16x8 read_operand(const char* tile, const int (&bas
 }
 
 template <bool A_KC, bool B_KC>
-__device__ __forceinline__ void read_frags(bf16x8 (&af)[4], bf16x8 (&bf)[4], const char* stage, const int (&abase)[4],
+__device__ __forceinline__ void read_frags(bf16x8 (&af)[4], bf16x8 (&bf)[4], const char* slot, const int (&abase)[4],
                                            const int (&bbase)[4], int kk) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) af[t] = read_operand<A_KC>(stage, abase, t, kk);
+    for (int t = 0; t < 4; ++t) af[t] = read_operand<A_KC>(slot, abase, t, kk);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) bf[t] = read_operand<B_KC>(stage + TILE_BYTES, bbase, t, kk);
+    for (int t = 0; t < 4; ++t) bf[t] = read_operand<B_KC>(slot + HALF_OP_BYTES, bbase, t, kk);
 }
 
 template <Epi EPI>
 __device__ __forceinline__ void mfma_step(floatx16 (&acc)[4][4], const bf16x8 (&af)[4], const bf16x8 (&bf)[4]) {
     // Column by column in a snake, so that only one of the two operands changes between
-    // consecutive MFMAs (less switching on the operand paths; the kernel is power limited: +1 %).
+    // consecutive MFMAs (less switching on the operand paths; the kernel is power limited).
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -192,6 +219,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     const unsigned b_bytes = (unsigned)(B_KC ? g.N : g.K) * (unsigned)g.ldb * 2u;
     const unsigned a_kstep = A_KC ? (unsigned)BK * 2u : (unsigned)BK * (unsigned)g.lda * 2u;
     const unsigned b_kstep = B_KC ? (unsigned)BK * 2u : (unsigned)BK * (unsigned)g.ldb * 2u;
+    const unsigned a_half = a_kstep >> 1, b_half = b_kstep >> 1;
 
     int abase[4], bbase[4];
     frag_offsets<A_KC>(abase, wm, lane);
@@ -222,9 +250,9 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
             for (int r = 0; r < 16; ++r) { float z; asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(z)); acc[i][j][r] = z; }
     if (EPI == Epi::FwdStats && n0 + BN > g.N) init_acc_ragged<4, 2>(acc, g.N, tile_n);
 
-    unsigned avoff[8], bvoff[8];
-    tile_voffsets<A_KC>(avoff, m0, g.lda, wave, lane);
-    tile_voffsets<B_KC>(bvoff, n0, g.ldb, wave, lane);
+    unsigned avoff[4], bvoff[4];
+    half_voffsets<A_KC>(avoff, m0, g.lda, wave, lane);
+    half_voffsets<B_KC>(bvoff, n0, g.ldb, wave, lane);
 
     const int nkt = (g.K + BK - 1) / BK;
 
@@ -234,95 +262,123 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
 #define VP_SCHED_VMEM(n) __builtin_amdgcn_sched_group_barrier(0x020, n, 0)
     constexpr int DS_PER_STEP = (A_KC ? 4 : 8) + (B_KC ? 4 : 8);   // LDS reads per 16-wide k sub-step
 
-    // prologue: tile 0 -> stage 0 completely, then the first half of tile 1 -> stage 1
-    issue_loads<0, 16>(g, a_bytes, b_bytes, 0u, 0u, avoff, bvoff, g_stage0, wave);
-    __syncthreads();
-    trace_stamp<TRACE>(g, tile_idx, 1);
-    issue_loads<0, 8>(g, a_bytes, b_bytes, a_kstep, b_kstep, avoff, bvoff, g_stage1, wave);
-    bf16x8 af0[4], bf0[4], af1[4], bf1[4];
-    read_frags<A_KC, B_KC>(af0, bf0, g_stage0, abase, bbase, 0);
+    // Loads of k tile T into the slots (2T) % 5 and (2T + 1) % 5.
+#define VP_LOAD_A(T, S0, S1) issue_operand_loads<false, S0, S1>(g.A, a_bytes, (unsigned)(T) * a_kstep, a_half, avoff, wave)
+#define VP_LOAD_B(T, S0, S1) issue_operand_loads<true, S0, S1>(g.B, b_bytes, (unsigned)(T) * b_kstep, b_half, bvoff, wave)
+    // Waits (s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, lgkmcnt in bits 11:8, expcnt 6:4 left at 7).
+#define VP_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)                 /* lgkmcnt(0), vmcnt(63) */
+#define VP_WAIT_VM16_LGKM0() __builtin_amdgcn_s_waitcnt(0x4070)            /* vmcnt(16) lgkmcnt(0) */
+#define VP_BARRIER()                          \
+    asm volatile("" ::: "memory");            \
+    __builtin_amdgcn_s_barrier();             \
+    asm volatile("" ::: "memory")
 
-    // The k loop alternates two regions per 64-wide k tile T held in stage `cur`:
-    //  region 1: sub-steps 0..2 of tile T.  The loads 8..15 of tile T+1 (towards `nxt`) are spread
-    //            over sub-step 0, one every two MFMAs, so that no wavefront sits in the (in-order)
-    //            issue of a burst of global loads while its MFMA pipe runs dry.  It ends with the
-    //            only barrier of the tile: tile T+1 has landed, and every wavefront has fetched
-    //            its last operands from `cur`.
-    //  region 2: sub-step 3 of tile T, during which the first operands of tile T+1 are fetched
-    //            from `nxt` and the first eight loads of tile T+2 start streaming into `cur`.
-    // All sixteen loads of a tile are thus issued within the two sub-steps that follow the
-    // barrier freeing their stage, which leaves the last of them two sub-steps (about 1000
-    // cycles) to land before the next barrier; issuing part of them one sub-step later costs
-    // 4-8 % (measured), because the wavefronts then wait for memory at the barrier.
-    // Loads past the end of K hit an empty descriptor and cost nothing.  The loop's back edge
-    // sits right after a barrier, where no load is in flight.
+    // prologue: k tiles 0 and 1 are requested at once; tile 0 has landed after the first 16 of the 32 loads
+    VP_LOAD_A(0, 0, 1);
+    VP_LOAD_B(0, 0, 1);
+    VP_LOAD_A(1, 2, 3);
+    VP_LOAD_B(1, 2, 3);
+    VP_WAIT_VM16_LGKM0();
+    VP_BARRIER();
+    trace_stamp<TRACE>(g, tile_idx, 1);
+    bf16x8 af0[4], bf0[4], af1[4], bf1[4];
+    read_frags<A_KC, B_KC>(af0, bf0, lds_slot<0>(), abase, bbase, 0);
+
+    // One k tile T = four 16-wide sub-steps, operands fetched one sub-step ahead into the other register
+    // set.  M = T % 5 fixes the slots: first half H0 = 2M % 5, second half H1 = (2M+1) % 5, first half
+    // of the next tile NX = (2M+2) % 5; the loads of tile T + 2 go to L0 = (2M+4) % 5 (the spare slot,
+    // last read before the previous tile's second barrier) and L1 = (2M+5) % 5 = H0.
+    //   sub-step 0: last reads of H0, then barrier 1: every wavefront is done with H0.
+    //   sub-steps 1, 2: the 16 loads of tile T + 2, one every two MFMAs (the rate the texture-address
+    //            unit sustains; a burst stalls the in-order wavefront), A pairs then B pairs.  Sub-step 2
+    //            ends with barrier 2, after waiting for all but those 16 loads: tile T + 1 has landed
+    //            (it was requested one tile period ago), and every wavefront is done with H1.
+    //   sub-step 3: first operands of tile T + 1 from NX.
 #define VP_MIX_LOADS()   /* 16 MFMAs, the sub-step's operand reads and 8 global loads */              \
     _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                                       \
         VP_SCHED_MFMA(2);                                                                                \
         VP_SCHED_DSRD((DS_PER_STEP + 7) / 8);                                                            \
         VP_SCHED_VMEM(1);                                                                                \
     }
-#define VP_REGION1(cur, nxt, T)                                                                          \
+#define VP_TILE(M, T)                                                                                    \
     {                                                                                                    \
-        read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 1);                                           \
-        issue_loads<8, 16>(g, a_bytes, b_bytes, (unsigned)((T) + 1) * a_kstep, (unsigned)((T) + 1) * b_kstep, \
-                           avoff, bvoff, nxt, wave);                                                      \
-        mfma_step<EPI>(acc, af0, bf0);                                                                   \
-        VP_MIX_LOADS()                                                                                   \
-        read_frags<A_KC, B_KC>(af0, bf0, cur, abase, bbase, 2);                                           \
-        mfma_step<EPI>(acc, af1, bf1);                                                                   \
-        _Pragma("unroll") for (int q = 0; q < 5; ++q) {                                                   \
-            VP_SCHED_MFMA(3);                                                                            \
-            VP_SCHED_DSRD((DS_PER_STEP + 4) / 5);                                                        \
-        }                                                                                                \
-        VP_SCHED_MFMA(1);                                                                                \
-        read_frags<A_KC, B_KC>(af1, bf1, cur, abase, bbase, 3);                                           \
+        constexpr int H0 = (2 * (M)) % 5, H1 = (2 * (M) + 1) % 5, NX = (2 * (M) + 2) % 5, L0 = (2 * (M) + 4) % 5; \
+        opaque_offsets<A_KC>(abase);   /* keeps "slot address + lane offset" sums from being hoisted out of */ \
+        opaque_offsets<B_KC>(bbase);   /* the loop for all five slots at once (they would spill)            */ \
+        read_frags<A_KC, B_KC>(af1, bf1, lds_slot<H0>(), abase, bbase, 1);                                \
         mfma_step<EPI>(acc, af0, bf0);                                                                   \
         _Pragma("unroll") for (int q = 0; q < 4; ++q) {   /* operand reads early: they must have */     \
             VP_SCHED_MFMA(1);                               /* landed when the barrier is reached  */     \
             VP_SCHED_DSRD((DS_PER_STEP + 3) / 4);                                                        \
         }                                                                                                \
         VP_SCHED_MFMA(12);                                                                               \
-        __syncthreads();                                                                                 \
-    }
-#define VP_REGION2(cur, nxt, T)                                                                          \
-    {                                                                                                    \
-        read_frags<A_KC, B_KC>(af0, bf0, nxt, abase, bbase, 0);                                           \
-        issue_loads<0, 8>(g, a_bytes, b_bytes, (unsigned)((T) + 2) * a_kstep, (unsigned)((T) + 2) * b_kstep, \
-                          avoff, bvoff, cur, wave);                                                       \
+        VP_WAIT_LGKM0();                                                                                 \
+        VP_BARRIER();                                                                                    \
+        read_frags<A_KC, B_KC>(af0, bf0, lds_slot<H1>(), abase, bbase, 0);                                \
+        VP_LOAD_A((T) + 2, L0, H0);                                                                      \
         mfma_step<EPI>(acc, af1, bf1);                                                                   \
         VP_MIX_LOADS()                                                                                   \
+        read_frags<A_KC, B_KC>(af1, bf1, lds_slot<H1>(), abase, bbase, 1);                                \
+        VP_LOAD_B((T) + 2, L0, H0);                                                                      \
+        mfma_step<EPI>(acc, af0, bf0);                                                                   \
+        VP_MIX_LOADS()                                                                                   \
+        VP_WAIT_VM16_LGKM0();                                                                            \
+        VP_BARRIER();                                                                                    \
+        read_frags<A_KC, B_KC>(af0, bf0, lds_slot<NX>(), abase, bbase, 0);                                \
+        mfma_step<EPI>(acc, af1, bf1);                                                                   \
+        _Pragma("unroll") for (int q = 0; q < 5; ++q) {                                                   \
+            VP_SCHED_MFMA(3);                                                                            \
+            VP_SCHED_DSRD((DS_PER_STEP + 4) / 5);                                                        \
+        }                                                                                                \
+        VP_SCHED_MFMA(1);                                                                                \
     }
 
-    VP_REGION1(g_stage0, g_stage1, 0)
+    // The period of the slot assignment is five tiles: whole periods in a loop without exits (the state of
+    // loads in flight is the same at its entry and at its back edge: tile T + 1 on its way into slots 2
+    // and 3), the remaining nkt % 5 tiles as straight-line code behind it.
     int kt = 0;
-    for (; kt + 2 < nkt; kt += 2) {
-        VP_REGION2(g_stage0, g_stage1, kt)
-        VP_REGION1(g_stage1, g_stage0, kt + 1)
-        VP_REGION2(g_stage1, g_stage0, kt + 1)
-        VP_REGION1(g_stage0, g_stage1, kt + 2)
+    for (int it = nkt / 5; it > 0; --it) {
+        VP_TILE(0, kt)
+        VP_TILE(1, kt + 1)
+        VP_TILE(2, kt + 2)
+        VP_TILE(3, kt + 3)
+        VP_TILE(4, kt + 4)
+        kt += 5;
     }
-    // tile kt sits in stage 0 with region 1 done; at most one more tile follows
-    VP_REGION2(g_stage0, g_stage1, kt)
-    if (kt + 1 < nkt) {
-        VP_REGION1(g_stage1, g_stage0, kt + 1)
-        VP_REGION2(g_stage1, g_stage0, kt + 1)
+    {
+        const int rem = nkt - kt;
+        if (rem > 0) {
+            VP_TILE(0, kt)
+            if (rem > 1) {
+                VP_TILE(1, kt + 1)
+                if (rem > 2) {
+                    VP_TILE(2, kt + 2)
+                    if (rem > 3) {
+                        VP_TILE(3, kt + 3)
+                    }
+                }
+            }
+        }
     }
-#undef VP_REGION1
+#undef VP_TILE
 #undef VP_MIX_LOADS
-#undef VP_REGION2
+#undef VP_LOAD_A
+#undef VP_LOAD_B
+#undef VP_WAIT_LGKM0
+#undef VP_WAIT_VM16_LGKM0
+#undef VP_BARRIER
 #undef VP_SCHED_MFMA
 #undef VP_SCHED_DSRD
 #undef VP_SCHED_VMEM
-    __syncthreads();   // every wavefront is done with the stages before the epilogue reuses them
+    __syncthreads();   // every wavefront is done with the slots, and no load is in flight, before the epilogue reuses them
     trace_stamp<TRACE>(g, tile_idx, 2);
 
     // keep the epilogue's address arithmetic from being hoisted above the main loop, where it
     // would occupy registers (and spill) for the whole kernel
     asm volatile("" : "+s"(tile_m), "+s"(tile_n));
-    gemm_epilogue<EPI, 4, 2, STREAM>(acc, g, tile_m, tile_n, g_stage0,
-                                     wave < 2 ? g_stage0 + EPI_XCHG_BYTES + wave * StageF32<128>::BYTES
-                                              : g_stage1 + (wave - 2) * StageF32<128>::BYTES);
+    // exchange area at the start of slot 0; staging block of wavefront w in slot w (behind the exchange area in slot 0)
+    gemm_epilogue<EPI, 4, 2, STREAM>(acc, g, tile_m, tile_n, g_slot0,
+                                     wave == 0 ? g_slot0 + EPI_XCHG_BYTES : wave == 1 ? g_slot1 : wave == 2 ? g_slot2 : g_slot3);
     __syncthreads();   // the epilogue's LDS exchange is over before the next tile streams in
     trace_stamp<TRACE>(g, tile_idx, 3);
     }   // persistent tile loop
