@@ -239,17 +239,6 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     tile_of_block(v, gridDim.x, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    // accumulators are zeroed directly in the AGPR half of the register file: zeroing them as
-    // ordinary vectors first would need 256 more VGPRs for a moment and spill everything else
-    floatx16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { float z; asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(z)); acc[i][j][r] = z; }
-    if (EPI == Epi::FwdStats && n0 + BN > g.N) init_acc_ragged<4, 2>(acc, g.N, tile_n);
-
     unsigned avoff[4], bvoff[4];
     half_voffsets<A_KC>(avoff, m0, g.lda, wave, lane);
     half_voffsets<B_KC>(bvoff, n0, g.ldb, wave, lane);
@@ -278,6 +267,19 @@ __global__ __launch_bounds__(NT) void gemm_bf16_fast_kernel(GemmBf16Params g) {
     VP_LOAD_B(0, 0, 1);
     VP_LOAD_A(1, 2, 3);
     VP_LOAD_B(1, 2, 3);
+    asm volatile("" ::: "memory");
+    // (while those loads are on their way)
+    // accumulators are zeroed directly in the AGPR half of the register file: zeroing them as
+    // ordinary vectors first would need 256 more VGPRs for a moment and spill everything else
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { float z; asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(z)); acc[i][j][r] = z; }
+    if (EPI == Epi::FwdStats && n0 + BN > g.N) init_acc_ragged<4, 2>(acc, g.N, tile_n);
+
     VP_WAIT_VM16_LGKM0();
     VP_BARRIER();
     trace_stamp<TRACE>(g, tile_idx, 1);
