@@ -35,12 +35,12 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 # runs reads 0.5x its size on FETCH_SIZE and 1.0x on WRITE_SIZE, hence the factors.
 PMC_FETCH_FACTOR, PMC_WRITE_FACTOR = 2.0, 1.0
 PMC_KIB = {   # kernel -> (FETCH_SIZE, WRITE_SIZE); dH is the accumulating launch (all shards but the first)
-    "cfg2_llama": {"gemm_bf16_fwd_stats": (100811.7, 36882.1), "gemm_bf16_dH": (134515.7, 66816.0),
-                   "gemm_bf16_dW": (98481.1, 64000.0)},
-    "cfg3_large_vocab": {"gemm_bf16_fwd_stats": (482860.5, 143630.4), "gemm_bf16_dH": (459801.5, 66816.0),
-                         "gemm_bf16_dW": (397501.3, 256959.8)},
-    "cfg4_very_large_vocab": {"gemm_bf16_fwd_stats": (1055409.1, 6375.3), "gemm_bf16_dlogits": (1077840.5, 131859.2),
-                              "gemm_bf16_dH": (837516.9, 132566.1), "gemm_bf16_dW": (884055.2, 513068.6)},
+    "cfg2_llama": {"gemm_bf16_fwd_stats": (106407.0, 46354.1), "gemm_bf16_dH": (132114.7, 80896.0),
+                   "gemm_bf16_dW": (99353.0, 80384.0)},
+    "cfg3_large_vocab": {"gemm_bf16_fwd_stats": (443979.2, 189183.5), "gemm_bf16_dH": (420997.1, 80896.0),
+                         "gemm_bf16_dW": (404757.8, 309940.4)},
+    "cfg4_very_large_vocab": {"gemm_bf16_fwd_stats": (859749.0, 51943.3), "gemm_bf16_dlogits": (856499.4, 177420.7),
+                              "gemm_bf16_dH": (837983.0, 158828.7), "gemm_bf16_dW": (945260.4, 615018.7)},
 }
 METRIC = "vocab-layer fwd+bwd TFLOP/s and tokens/s per GPU; % of bf16 MFMA peak"
 
