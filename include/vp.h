@@ -213,7 +213,7 @@ vp_status vp_embed_fwd(const void* table_shard, const int64_t* ids,
  * Input layer backward on one shard (appendix C): scatter-add of the output gradient,
  *     dtable_shard[ids[i] - shard_offset, :] += (float) grad_out[i, :]   for owned ids,
  * with repeated ids accumulated in increasing token position i.  No atomics: tokens are
- * grouped by row with a sort and every row is summed by one workgroup, so the result is
+ * grouped by row with a sort and every row is summed, per slab of columns, by one workgroup, so the result is
  * bit-identical from run to run.
  *   grad_out [N,h] : in, type dt.  dtable_shard [Vs,h] : in/out, fp32, accumulate.
  * Limit: N <= 2^24.

@@ -56,6 +56,8 @@ def check_embed(N, h, V, p, dtype, seed, ids=None, preload=False):
     (129, 36, 96, 3),        # bf16 rows of 72 bytes: not a multiple of 16 -> scalar path
     (1, 8, 16, 2),
     (20000, 64, 5000, 2),    # more keys than one sorting workgroup holds (multi-chunk sort)
+    (8192, 200, 32, 2),      # the one-kernel path at its largest N; runs far longer than a workgroup's chunk; ragged slab
+    (3000, 37, 64, 2),       # odd row length: one column per lane
 ])
 def test_embed_small_cases(shape, dtype):
     N, h, V, p = shape
@@ -109,6 +111,19 @@ def test_cfg5_embedding_full_size():
     # the sum over shards is the plain lookup
     full_table = np.concatenate(tables)
     assert np.array_equal(total, si.bf16_bits_to_f32(full_table[ids]))
+
+
+def test_embed_key_packing_limits():
+    # the one-kernel path packs (row, token) into 32 bits: 13 bits of token, 2^19 - 1 rows per shard; one row more
+    # per shard takes the general path.  (N * Vs < 2^31 is the library's limit, hence N = 4000 here.)
+    N, h = 4000, 8
+    for Vs in (2 ** 19 - 1, 2 ** 19):
+        ids = si.uniform_ids(N, 2 * Vs, 31)
+        ids[-1] = Vs - 1
+        ids[-2] = 2 * Vs - 1
+        ids[:40] = Vs - 1          # and a long run on that row
+        print("embed key limits Vs", Vs, flush=True)
+        check_embed(N, h, 2 * Vs, 2, "bf16", seed=31, ids=ids)
 
 
 def test_embed_more_than_65535_tokens():
